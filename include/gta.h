@@ -1,0 +1,151 @@
+/*
+ * libgta -- Grouped-head latenT Attention (GTA, arXiv 2506.17286) attention forward pass for
+ * AMD MI355X (gfx950).  C ABI: plain structs, plain pointers, sizes; no C++ or framework types.
+ *
+ * Notation follows the paper (Sec. 3.2): H = d_model, n_h heads, n_q attention-map (query)
+ * groups, n_k key groups, n_c latent-value groups, d_h head dim, d_l latent dim (d_l >= d_h).
+ * Row-vector convention: projections are x . W with W stored row-major [in, out].
+ *
+ * Group maps (the paper leaves q(i), k(i), c(i) open; contiguous blocks are used):
+ *   q(i) = i / (n_h / n_q),   k(g) = g / (n_q / n_k),   c(g) = g / (n_q / n_c),
+ * so n_k | n_q | n_h and n_c | n_q are required.
+ *
+ * Conventions for every entry point
+ *   - Pointers marked "device" are HIP device memory owned by the caller, 16-byte aligned,
+ *     dense row-major.  Config/weight/cache structs are host memory, read only during the call.
+ *   - The library allocates, frees and retains nothing.  Scratch memory comes in through
+ *     `workspace` (device), sized by gta_workspace_bytes().
+ *   - All work is enqueued on `hip_stream` (a hipStream_t passed as void*; NULL = the null
+ *     stream).  No call synchronises with the host.
+ *   - Return value: GTA_OK or a negative gta_status.  On a host-detected error nothing has been
+ *     enqueued or written.  A sequence whose new rows would not fit its cache slot is detected on
+ *     the device: nothing is stored for it, its output rows are zero-filled and
+ *     cache->status[slot] is set to GTA_ERR_CACHE_FULL.
+ *   - Re-entrant; no global state.  Two calls that touch the same cache slot, output or
+ *     workspace must be ordered by the caller (same stream or events).
+ */
+#ifndef GTA_H_
+#define GTA_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define GTA_API __attribute__((visibility("default")))
+
+typedef enum {
+  GTA_OK = 0,
+  GTA_ERR_NULL = -1,        /* a required pointer is NULL */
+  GTA_ERR_SHAPE = -2,       /* divisibility / range violation (n_q % n_k, d_l < d_h, batch <= 0 ...) */
+  GTA_ERR_ALIGN = -3,       /* a device pointer is not 16-byte aligned */
+  GTA_ERR_DTYPE = -4,       /* unknown dtype / gate / rope code */
+  GTA_ERR_UNSUPPORTED = -5, /* dimensions outside what the kernels handle */
+  GTA_ERR_WORKSPACE = -6,   /* workspace NULL or smaller than gta_workspace_bytes() */
+  GTA_ERR_HIP = -7,         /* a kernel launch failed (hipGetLastError) */
+  GTA_ERR_CACHE_FULL = -8   /* device-side: written to cache->status[slot] */
+} gta_status;
+
+enum { GTA_F32 = 0, GTA_BF16 = 1 };            /* gta_config.dtype */
+enum { GTA_GATE_SIGMOID = 0, GTA_GATE_OFF = 1 }; /* gta_config.gate  */
+enum { GTA_MODE_PREFILL = 0, GTA_MODE_DECODE = 1 };
+
+/* Hyper-parameters of one GTA layer (Sec. 3.2).  Host memory. */
+typedef struct {
+  int32_t d_model;       /* H */
+  int32_t n_heads;       /* n_h */
+  int32_t n_qgroups;     /* n_q: attention maps per token */
+  int32_t n_kgroups;     /* n_k */
+  int32_t n_cgroups;     /* n_c */
+  int32_t head_dim;      /* d_h */
+  int32_t latent_dim;    /* d_l per latent group */
+  int32_t dtype;         /* GTA_F32 | GTA_BF16: element type of x, weights, caches and out.
+                            Accumulation, softmax statistics and the gate are always fp32. */
+  int32_t rope;          /* 0 = none; 1 = rotate-half RoPE on q and k (App. B.1.1): pair
+                            (j, j + d_h/2) turns by pos * rope_base^(-2j/d_h); the latent value is
+                            never rotated.  Positions count from 0 within each sequence. */
+  float   rope_base;     /* e.g. 10000 */
+  int32_t gate;          /* GTA_GATE_SIGMOID (Sec. 3.2) | GTA_GATE_OFF (factor 1; for tests) */
+  float   softmax_scale; /* 0 => 1/sqrt(d_h) (Sec. 3.3) */
+} gta_config;
+
+/* Layer weights (Sec. 3.2, 3.3).  Struct in host memory, pointers device, element type = dtype. */
+typedef struct {
+  const void *wq;  /* [H, n_q*d_h] */
+  const void *wk;  /* [H, n_k*d_h] */
+  const void *wc;  /* [H, n_c*d_l] */
+  const void *wg;  /* [H, n_h*d_h]   W_{G,i} = columns [i*d_h, (i+1)*d_h) */
+  const void *wp;  /* [n_h, d_l, d_h] W_{P,i} */
+  const void *wo;  /* [n_h*d_h, H], or NULL: the output is the concatenated gated heads */
+} gta_weights;
+
+/* Contiguous grouped-key / latent-value caches (Sec. 3.3, App. B.1.3).  Struct host, arrays
+ * device.  Slot s holds seq_lens[s] valid tokens in rows 0..seq_lens[s]-1; row p is position p. */
+typedef struct {
+  void    *k;         /* [max_batch, max_seq, n_k*d_h]  keys after RoPE */
+  void    *c;         /* [max_batch, max_seq, n_c*d_l]  latent values (no RoPE) */
+  int32_t *seq_lens;  /* [max_batch] */
+  int32_t *status;    /* [max_batch]; kernels write it only to flag a slot (GTA_ERR_CACHE_FULL,
+                         GTA_ERR_SHAPE), never to clear it */
+  int32_t  max_batch;
+  int32_t  max_seq;
+} gta_cache;
+
+/* Bytes of device workspace the call described by the arguments needs.
+ *   mode PREFILL: batch sequences, total_tokens packed tokens, longest sequence <= max_len.
+ *   mode DECODE : batch sequences, max_len = cache->max_seq, num_splits as passed to gta_decode
+ *                 (0 = library's choice).
+ * Returns 0 if cfg is NULL or invalid. */
+GTA_API size_t gta_workspace_bytes(const gta_config *cfg, int mode, int32_t batch, int64_t total_tokens,
+                           int32_t max_len, int32_t num_splits);
+
+/* Causal prefill (Sec. 3.2-3.3; per-token form App. B.1.1-B.1.2) of `batch` packed sequences.
+ *   x           device [total_tokens, H]
+ *   cu_seqlens  device [batch+1] token offsets (cu[0] = 0, cu[batch] = total_tokens), or NULL:
+ *               batch equal sequences of total_tokens / batch tokens
+ *   max_seqlen  host upper bound of the longest sequence (sizes the launch)
+ *   cache       NULL, or the caches to fill: rows 0..T_b-1 of slot slots[b] receive the keys
+ *               (after RoPE) and latent values of sequence b and seq_lens[slot] is SET to T_b
+ *               (a fresh prefill; requires max_seqlen <= cache->max_seq)
+ *   slots       device [batch] slot of each sequence, or NULL for slot b = b
+ *   out         device [total_tokens, n_h*d_h]; [total_tokens, H] when weights->wo is set */
+GTA_API int gta_prefill(const gta_config *cfg, const gta_weights *weights, const void *x,
+                const int32_t *cu_seqlens, int32_t batch, int64_t total_tokens,
+                int32_t max_seqlen, const gta_cache *cache, const int32_t *slots, void *out,
+                void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* One decode step (App. B.1.3) for `batch` sequences: project x_new, rotate q and k at position
+ * seq_lens[slot], append k and c as row seq_lens[slot], increment seq_lens[slot], then attend
+ * over all rows of the slot including the new one; gate and decoder use the new token.
+ *   x_new       device [batch, H]
+ *   slots       device [batch] distinct slots, or NULL for slot b = b
+ *   out         device [batch, n_h*d_h] (or [batch, H] with wo)
+ *   num_splits  context splits per sequence (split-K); 0 = library's choice */
+GTA_API int gta_decode(const gta_config *cfg, const gta_weights *weights, const void *x_new,
+               int32_t batch, const gta_cache *cache, const int32_t *slots, void *out,
+               int32_t num_splits, void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Append already projected (and rotated) rows to the caches (App. B.1.3): pure data movement,
+ * bit-exact.  Rows [cu_new[b], cu_new[b+1]) of k_new / c_new go to slot slots[b] at positions
+ * seq_lens[slot].., then seq_lens[slot] += their count.
+ *   k_new   device [total_new, n_k*d_h];  c_new  device [total_new, n_c*d_l]
+ *   cu_new  device [batch+1];  slots device [batch] distinct slots or NULL
+ *   max_new host upper bound of rows per sequence (sizes the launch); a sequence with more rows
+ *           is skipped and its slot's status is set to GTA_ERR_SHAPE */
+GTA_API int gta_cache_append(const gta_config *cfg, const gta_cache *cache, const int32_t *slots,
+                     const void *k_new, const void *c_new, const int32_t *cu_new, int32_t batch,
+                     int32_t max_new, void *hip_stream);
+
+/* Static string for a gta_status value. */
+GTA_API const char *gta_strerror(int code);
+
+/* 1 if the configuration runs on the tuned bf16 MFMA/streaming kernels, 0 if it runs on the
+ * shape-generic kernels (still HIP, any dimensions), negative gta_status if invalid. */
+GTA_API int gta_uses_tuned_kernels(const gta_config *cfg, int mode);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GTA_H_ */

@@ -1,0 +1,228 @@
+// C-ABI entry points of libgta: argument validation, workspace carve-up and dispatch to the
+// tuned bf16 kernels or the shape-generic kernels.  No device code in this file.
+#include <math.h>
+
+#include "gta_internal.h"
+#include "gta_tuned.h"
+
+namespace gta {
+
+static int make_dims(const gta_config *c, Dims *out) {
+  if (!c) return GTA_ERR_NULL;
+  if (c->dtype != GTA_F32 && c->dtype != GTA_BF16) return GTA_ERR_DTYPE;
+  if (c->gate != GTA_GATE_SIGMOID && c->gate != GTA_GATE_OFF) return GTA_ERR_DTYPE;
+  if (c->rope != 0 && c->rope != 1) return GTA_ERR_DTYPE;
+  if (c->d_model <= 0 || c->n_heads <= 0 || c->n_qgroups <= 0 || c->n_kgroups <= 0 || c->n_cgroups <= 0 ||
+      c->head_dim <= 0 || c->latent_dim <= 0)
+    return GTA_ERR_SHAPE;
+  if (c->n_heads % c->n_qgroups || c->n_qgroups % c->n_kgroups || c->n_qgroups % c->n_cgroups) return GTA_ERR_SHAPE;
+  if (c->latent_dim < c->head_dim) return GTA_ERR_SHAPE;  // Sec. 3.2: d_l >= d_h
+  if (c->rope && (c->head_dim % 2 || !(c->rope_base > 0.f))) return GTA_ERR_SHAPE;
+  if (!(c->softmax_scale >= 0.f)) return GTA_ERR_SHAPE;
+  const int64_t wtot = (int64_t)(c->n_qgroups + c->n_kgroups + c->n_heads) * c->head_dim +
+                       (int64_t)c->n_cgroups * c->latent_dim;
+  if (wtot > (1 << 24) || c->d_model > (1 << 24) || (int64_t)c->n_qgroups * c->latent_dim > (1 << 24))
+    return GTA_ERR_UNSUPPORTED;
+  Dims d{};
+  d.H = c->d_model; d.nh = c->n_heads; d.nq = c->n_qgroups; d.nk = c->n_kgroups; d.nc = c->n_cgroups;
+  d.dh = c->head_dim; d.dl = c->latent_dim;
+  d.hpq = d.nh / d.nq; d.qpk = d.nq / d.nk; d.qpc = d.nq / d.nc;
+  d.wq_w = d.nq * d.dh; d.wk_w = d.nk * d.dh; d.wc_w = d.nc * d.dl; d.wg_w = d.nh * d.dh;
+  d.wtot = (int)wtot;
+  d.dtype = c->dtype; d.rope = c->rope; d.gate = c->gate == GTA_GATE_SIGMOID ? 1 : 0;
+  d.scale = c->softmax_scale > 0.f ? c->softmax_scale : (float)(1.0 / sqrt((double)c->head_dim));
+  d.rope_base = (double)c->rope_base;
+  *out = d;
+  return GTA_OK;
+}
+
+static inline bool misaligned(const void *p) { return ((uintptr_t)p & 15u) != 0; }
+
+// ---------------------------------------------------------------------------- workspace layout
+namespace {
+struct Carver {
+  char *base; size_t off = 0;
+  explicit Carver(void *b) : base((char *)b) {}
+  template <typename T> T *take(size_t bytes) {
+    T *p = base ? (T *)(base + off) : nullptr;
+    off += align_up(bytes);
+    return p;
+  }
+};
+}  // namespace
+
+PrefillWs carve_prefill(const Dims &d, bool tuned, bool with_wo, int batch, int64_t total, int max_len, void *base) {
+  (void)batch;
+  Carver cv(base);
+  PrefillWs w{};
+  const size_t n = (size_t)total, es = (size_t)d.esize();
+  w.seq_id = cv.take<int32_t>(n * 4);
+  w.pos = cv.take<int32_t>(n * 4);
+  w.rope = cv.take<float2>(d.rope ? (size_t)max_len * (d.dh / 2) * sizeof(float2) : 0);
+  w.praw = cv.take<float>(tuned ? 0 : n * d.wtot * 4);
+  w.q = cv.take<void>(n * d.wq_w * es);
+  w.k = cv.take<void>(n * d.wk_w * es);
+  w.c = cv.take<void>(n * d.wc_w * es);
+  w.g = cv.take<void>(n * d.wg_w * (tuned ? es : 4));
+  w.l = cv.take<void>(n * (size_t)d.nq * d.dl * (tuned ? es : 4));
+  w.o = cv.take<void>(with_wo ? n * d.wg_w * (tuned ? es : 4) : 0);
+  w.bytes = cv.off;
+  return w;
+}
+
+int choose_splits(const Dims &d, int batch, int max_seq, int requested) {
+  (void)d;
+  if (requested > 0) return requested > 1024 ? 1024 : requested;
+  // enough (sequence, split) blocks to put ~2 on every one of the 256 CUs, but no split shorter
+  // than 256 cached rows.
+  int want = (512 + batch - 1) / batch;
+  int cap = max_seq / 256;
+  if (cap < 1) cap = 1;
+  int s = want < cap ? want : cap;
+  if (s < 1) s = 1;
+  if (s > 256) s = 256;
+  return s;
+}
+
+DecodeWs carve_decode(const Dims &d, bool with_wo, int batch, int splits, void *base) {
+  Carver cv(base);
+  DecodeWs w{};
+  const size_t b = (size_t)batch;
+  w.splits = splits;
+  w.praw = cv.take<float>(b * d.wtot * 4);
+  w.q = cv.take<float>(b * d.wq_w * 4);
+  w.g = cv.take<float>(b * d.wg_w * 4);
+  w.part = cv.take<float>(b * splits * d.nq * (size_t)(d.dl + 2) * 4);
+  w.l = cv.take<float>(b * d.nq * (size_t)d.dl * 4);
+  w.o = cv.take<float>(with_wo ? b * d.wg_w * 4 : 0);
+  w.oldlen = cv.take<int32_t>(b * 4);
+  w.bytes = cv.off;
+  return w;
+}
+
+static int check_weights(const gta_weights *w) {
+  if (!w || !w->wq || !w->wk || !w->wc || !w->wg || !w->wp) return GTA_ERR_NULL;
+  if (misaligned(w->wq) || misaligned(w->wk) || misaligned(w->wc) || misaligned(w->wg) || misaligned(w->wp) ||
+      misaligned(w->wo))
+    return GTA_ERR_ALIGN;
+  return GTA_OK;
+}
+
+static int check_cache(const gta_cache *c) {
+  if (!c->k || !c->c || !c->seq_lens || !c->status) return GTA_ERR_NULL;
+  if (c->max_batch <= 0 || c->max_seq <= 0) return GTA_ERR_SHAPE;
+  if (misaligned(c->k) || misaligned(c->c) || ((uintptr_t)c->seq_lens & 3u) || ((uintptr_t)c->status & 3u))
+    return GTA_ERR_ALIGN;
+  return GTA_OK;
+}
+
+static const int kMaxBatch = 65535;  // grid.y / grid.z limit
+
+}  // namespace gta
+
+using namespace gta;
+
+extern "C" {
+
+const char *gta_strerror(int code) {
+  switch (code) {
+    case GTA_OK: return "ok";
+    case GTA_ERR_NULL: return "a required pointer is NULL";
+    case GTA_ERR_SHAPE: return "shape / divisibility / range violation";
+    case GTA_ERR_ALIGN: return "device pointer not 16-byte aligned";
+    case GTA_ERR_DTYPE: return "unknown dtype, gate or rope code";
+    case GTA_ERR_UNSUPPORTED: return "dimensions not supported by the kernels";
+    case GTA_ERR_WORKSPACE: return "workspace missing or too small";
+    case GTA_ERR_HIP: return "HIP kernel launch failed";
+    case GTA_ERR_CACHE_FULL: return "cache slot full";
+    default: return "unknown gta_status";
+  }
+}
+
+int gta_uses_tuned_kernels(const gta_config *cfg, int mode) {
+  Dims d;
+  int rc = make_dims(cfg, &d);
+  if (rc != GTA_OK) return rc;
+  if (mode == GTA_MODE_PREFILL) return tuned_prefill_supported(d) ? 1 : 0;
+  if (mode == GTA_MODE_DECODE) return tuned_decode_supported(d) ? 1 : 0;
+  return GTA_ERR_DTYPE;
+}
+
+size_t gta_workspace_bytes(const gta_config *cfg, int mode, int32_t batch, int64_t total_tokens, int32_t max_len,
+                           int32_t num_splits) {
+  Dims d;
+  if (make_dims(cfg, &d) != GTA_OK || batch <= 0 || max_len < 0) return 0;
+  if (mode == GTA_MODE_PREFILL) {
+    if (total_tokens < 0) return 0;
+    // sized for a call with W_O (a superset of the call without)
+    return carve_prefill(d, tuned_prefill_supported(d), true, batch, total_tokens, max_len, nullptr).bytes + 256;
+  }
+  if (mode == GTA_MODE_DECODE) {
+    int splits = choose_splits(d, batch, max_len, num_splits);
+    return carve_decode(d, true, batch, splits, nullptr).bytes + 256;
+  }
+  return 0;
+}
+
+int gta_prefill(const gta_config *cfg, const gta_weights *weights, const void *x, const int32_t *cu_seqlens,
+                int32_t batch, int64_t total_tokens, int32_t max_seqlen, const gta_cache *cache,
+                const int32_t *slots, void *out, void *workspace, size_t workspace_bytes, void *hip_stream) {
+  Dims d;
+  int rc = make_dims(cfg, &d);
+  if (rc != GTA_OK) return rc;
+  if ((rc = check_weights(weights)) != GTA_OK) return rc;
+  if (!x || !out) return GTA_ERR_NULL;
+  if (batch <= 0 || batch > kMaxBatch || total_tokens < 0 || total_tokens > INT32_MAX || max_seqlen < 0)
+    return GTA_ERR_SHAPE;
+  if (!cu_seqlens && (total_tokens % batch != 0 || total_tokens / batch > max_seqlen)) return GTA_ERR_SHAPE;
+  if ((int64_t)total_tokens * d.wtot > ((int64_t)1 << 40)) return GTA_ERR_UNSUPPORTED;
+  if (misaligned(x) || misaligned(out) || ((uintptr_t)cu_seqlens & 3u) || ((uintptr_t)slots & 3u)) return GTA_ERR_ALIGN;
+  if (cache) {
+    if ((rc = check_cache(cache)) != GTA_OK) return rc;
+    if (max_seqlen > cache->max_seq || (!slots && batch > cache->max_batch)) return GTA_ERR_SHAPE;
+  }
+  if (total_tokens == 0 || max_seqlen == 0) return GTA_OK;
+  const bool tuned = tuned_prefill_supported(d);
+  if (!workspace || misaligned(workspace)) return GTA_ERR_WORKSPACE;
+  PrefillWs ws = carve_prefill(d, tuned, weights->wo != nullptr, batch, total_tokens, max_seqlen, workspace);
+  if (ws.bytes > workspace_bytes) return GTA_ERR_WORKSPACE;
+  hipStream_t st = (hipStream_t)hip_stream;
+  if (tuned)
+    return tuned_prefill(d, *weights, x, cu_seqlens, batch, total_tokens, max_seqlen, cache, slots, out, ws, st);
+  return generic_prefill(d, *weights, x, cu_seqlens, batch, total_tokens, max_seqlen, cache, slots, out, ws, st);
+}
+
+int gta_decode(const gta_config *cfg, const gta_weights *weights, const void *x_new, int32_t batch,
+               const gta_cache *cache, const int32_t *slots, void *out, int32_t num_splits, void *workspace,
+               size_t workspace_bytes, void *hip_stream) {
+  Dims d;
+  int rc = make_dims(cfg, &d);
+  if (rc != GTA_OK) return rc;
+  if ((rc = check_weights(weights)) != GTA_OK) return rc;
+  if (!x_new || !out || !cache) return GTA_ERR_NULL;
+  if ((rc = check_cache(cache)) != GTA_OK) return rc;
+  if (batch <= 0 || batch > kMaxBatch || num_splits < 0 || (!slots && batch > cache->max_batch)) return GTA_ERR_SHAPE;
+  if (misaligned(x_new) || misaligned(out) || ((uintptr_t)slots & 3u)) return GTA_ERR_ALIGN;
+  if (!workspace || misaligned(workspace)) return GTA_ERR_WORKSPACE;
+  const int splits = choose_splits(d, batch, cache->max_seq, num_splits);
+  DecodeWs ws = carve_decode(d, weights->wo != nullptr, batch, splits, workspace);
+  if (ws.bytes > workspace_bytes) return GTA_ERR_WORKSPACE;
+  hipStream_t st = (hipStream_t)hip_stream;
+  if (tuned_decode_supported(d)) return tuned_decode(d, *weights, x_new, batch, *cache, slots, out, ws, st);
+  return generic_decode(d, *weights, x_new, batch, *cache, slots, out, ws, st);
+}
+
+int gta_cache_append(const gta_config *cfg, const gta_cache *cache, const int32_t *slots, const void *k_new,
+                     const void *c_new, const int32_t *cu_new, int32_t batch, int32_t max_new, void *hip_stream) {
+  Dims d;
+  int rc = make_dims(cfg, &d);
+  if (rc != GTA_OK) return rc;
+  if (!cache || !k_new || !c_new || !cu_new) return GTA_ERR_NULL;
+  if ((rc = check_cache(cache)) != GTA_OK) return rc;
+  if (batch <= 0 || batch > kMaxBatch || max_new < 0 || max_new > (1 << 30) || (!slots && batch > cache->max_batch))
+    return GTA_ERR_SHAPE;
+  if (misaligned(k_new) || misaligned(c_new) || ((uintptr_t)cu_new & 3u) || ((uintptr_t)slots & 3u)) return GTA_ERR_ALIGN;
+  return generic_cache_append(d, *cache, slots, k_new, c_new, cu_new, batch, max_new, (hipStream_t)hip_stream);
+}
+
+}  // extern "C"

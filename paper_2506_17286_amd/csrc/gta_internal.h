@@ -1,0 +1,78 @@
+// Internal declarations shared by the translation units of libgta (not part of the C ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "gta.h"
+
+namespace gta {
+
+// Validated, derived view of a gta_config.
+struct Dims {
+  int H, nh, nq, nk, nc, dh, dl;
+  int hpq;          // heads per map group        n_h / n_q
+  int qpk;          // map groups per key group   n_q / n_k
+  int qpc;          // map groups per latent group n_q / n_c
+  int wq_w, wk_w, wc_w, wg_w;  // widths of Q, K, C and gate pre-activation rows
+  int wtot;         // wq_w + wk_w + wc_w + wg_w
+  int dtype;        // GTA_F32 | GTA_BF16
+  int rope;         // 0 | 1
+  int gate;         // 1 = sigmoid, 0 = off
+  float scale;      // softmax scale
+  double rope_base;
+  int esize() const { return dtype == GTA_BF16 ? 2 : 4; }
+};
+
+static inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
+
+// ---- workspace carve-up (one function per mode so sizing and use cannot disagree) ----------
+struct PrefillWs {
+  int32_t *seq_id, *pos;   // [total] sequence index and position of each packed token
+  float2 *rope;            // [max_len, d_h/2] (cos, sin)
+  float *praw;             // generic path: raw fp32 projections [total, wtot]
+  void *q, *k, *c;         // [total, wq_w], [total, wk_w], [total, wc_w]   element type = dtype
+  void *g;                 // gate pre-activation [total, wg_w]; fp32 (generic) or dtype (tuned)
+  void *l;                 // normalised group outputs [total, n_q*d_l]; fp32 (generic) or dtype
+  void *o;                 // gated heads [total, wg_w] (dtype), only with W_O
+  size_t bytes;
+};
+PrefillWs carve_prefill(const Dims &d, bool tuned, bool with_wo, int batch, int64_t total,
+                        int max_len, void *base);
+
+struct DecodeWs {
+  float *praw;             // [batch, wtot] raw fp32 projections of the new tokens
+  float *q;                // [batch, wq_w] rotated queries
+  float *g;                // [batch, wg_w] gate pre-activations
+  float *part;             // [batch, splits, n_q, d_l + 2]  (acc[d_l], m, l)
+  float *l;                // [batch, n_q*d_l]
+  float *o;                // [batch, wg_w] gated heads, only with W_O
+  int32_t *oldlen;         // [batch] tokens cached before the step, or -1 if the slot is full
+  size_t bytes;
+  int splits;
+};
+int choose_splits(const Dims &d, int batch, int max_seq, int requested);
+DecodeWs carve_decode(const Dims &d, bool with_wo, int batch, int splits, void *base);
+
+// ---- shape-generic path (any dims, fp32 or bf16 elements), gta_generic.hip ------------------
+int generic_prefill(const Dims &d, const gta_weights &w, const void *x, const int32_t *cu,
+                    int batch, int64_t total, int max_len, const gta_cache *cache,
+                    const int32_t *slots, void *out, const PrefillWs &ws, hipStream_t st);
+int generic_decode(const Dims &d, const gta_weights &w, const void *x_new, int batch,
+                   const gta_cache &cache, const int32_t *slots, void *out, const DecodeWs &ws,
+                   hipStream_t st);
+int generic_cache_append(const Dims &d, const gta_cache &cache, const int32_t *slots,
+                         const void *k_new, const void *c_new, const int32_t *cu_new, int batch,
+                         int max_new, hipStream_t st);
+
+// Helper kernels reused by the tuned path.
+void launch_rowmap(const int32_t *cu, int batch, int64_t total, int32_t *seq_id, int32_t *pos,
+                   hipStream_t st);
+void launch_rope_table(float2 *tab, int max_pos, int dh, double base, hipStream_t st);
+void launch_prefill_commit(const gta_cache &cache, const int32_t *slots, const int32_t *cu,
+                           int batch, int64_t total, hipStream_t st);
+
+static inline int check_launch() { return hipGetLastError() == hipSuccess ? GTA_OK : GTA_ERR_HIP; }
+
+}  // namespace gta

@@ -1,0 +1,106 @@
+"""Helpers of the GPU parity tests: upload seeded inputs, call the C ABI, compare with the oracle."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from oracle import gta_oracle as orc
+from paper_2506_17286_amd import binding as B
+
+# Tolerances of the parity gate.  fp32: max-abs 1e-5.  bf16 inputs with fp32 accumulation:
+# max-abs 2e-2 and relative RMS 5e-3 (bf16 rounding of Q, K, C, the softmax weights, the group
+# output and the result each contribute ~2^-9/sqrt(3) relative error).
+TOL = {"f32": dict(max_abs=1e-5, rel_rms=1e-5), "bf16": dict(max_abs=2e-2, rel_rms=5e-3)}
+
+
+def oracle_config(wl, gate=True) -> orc.OracleConfig:
+    return orc.OracleConfig(d_model=wl.d_model, n_heads=wl.n_heads, n_qgroups=wl.n_qgroups,
+                            n_kgroups=wl.n_kgroups, n_cgroups=wl.n_cgroups, head_dim=wl.head_dim,
+                            latent_dim=wl.latent_dim, rope=wl.rope, rope_base=wl.rope_base, gate=gate)
+
+
+def oracle_weights(w) -> orc.OracleWeights:
+    return orc.OracleWeights(w["wq"], w["wk"], w["wc"], w["wg"], w["wp"], w.get("wo")).f64()
+
+
+def upload_weights(w, dtype):
+    return {k: B.to_device(v, dtype) for k, v in w.items()}
+
+
+def f64(t: torch.Tensor) -> np.ndarray:
+    return t.detach().to(torch.float64).cpu().numpy()
+
+
+def errors(got: np.ndarray, ref: np.ndarray):
+    d = got.astype(np.float64) - ref
+    return float(np.abs(d).max()), float(np.linalg.norm(d) / max(np.linalg.norm(ref), 1e-300))
+
+
+def assert_close(got, ref, dtype, what=""):
+    assert np.all(np.isfinite(got)), f"{what}: non-finite values"
+    ma, rr = errors(got, ref)
+    tol = TOL[dtype]
+    assert ma <= tol["max_abs"] and rr <= tol["rel_rms"], \
+        f"{what}: max_abs {ma:.3e} (tol {tol['max_abs']:.0e}), rel_rms {rr:.3e} (tol {tol['rel_rms']:.0e})"
+    return ma, rr
+
+
+class DeviceCache:
+    """Caller-owned cache tensors plus the gta_cache struct that points at them."""
+
+    def __init__(self, wl, n_slots, max_seq, k=None, c=None, seq_lens=None, fill=None):
+        dt = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
+        kw, cw = wl.kv_width
+        if k is None:
+            k = torch.zeros((n_slots, max_seq, kw), dtype=dt, device="cuda")
+            c = torch.zeros((n_slots, max_seq, cw), dtype=dt, device="cuda")
+            if fill is not None:   # canary pattern in every row
+                k.fill_(fill); c.fill_(fill)
+        self.k, self.c = k, c
+        self.seq_lens = torch.zeros(n_slots, dtype=torch.int32, device="cuda") if seq_lens is None else seq_lens
+        self.status = torch.zeros(n_slots, dtype=torch.int32, device="cuda")
+        self.struct = B.make_cache(self.k, self.c, self.seq_lens, self.status)
+
+
+def run_prefill(wl, wdev, x_np, cu_np=None, batch=None, max_seqlen=None, cache: DeviceCache = None,
+                slots=None, gate=True, workspace=None):
+    """gta_prefill through the C ABI on numpy hidden states; returns the output tensor."""
+    cfg = B.config_of(wl)
+    if not gate:
+        cfg.gate = B.GTA_GATE_OFF
+    total = x_np.shape[0]
+    x = B.to_device(x_np, wl.dtype)
+    if cu_np is not None:
+        cu = torch.from_numpy(np.asarray(cu_np, dtype=np.int32)).cuda()
+        batch = len(cu_np) - 1
+        lens = np.diff(cu_np)
+        max_seqlen = int(lens.max()) if max_seqlen is None else max_seqlen
+    else:
+        cu = None
+        batch = batch or 1
+        max_seqlen = total // batch if max_seqlen is None else max_seqlen
+    width = wl.d_model if wdev.get("wo") is not None else wl.n_heads * wl.head_dim
+    out = torch.full((total, width), float("nan"), dtype=x.dtype, device="cuda")
+    nbytes = B.gta_workspace_bytes(cfg, B.GTA_MODE_PREFILL, batch, total, max_seqlen)
+    ws = workspace if workspace is not None else B.alloc_workspace(nbytes)
+    sl = None if slots is None else torch.from_numpy(np.asarray(slots, dtype=np.int32)).cuda()
+    B.gta_prefill(cfg, B.make_weights(wdev), x, cu, batch, total, max_seqlen,
+                  None if cache is None else cache.struct, sl, out, ws)
+    torch.cuda.synchronize()
+    return out
+
+
+def run_decode(wl, wdev, x_np, cache: DeviceCache, slots=None, num_splits=0, gate=True):
+    cfg = B.config_of(wl)
+    if not gate:
+        cfg.gate = B.GTA_GATE_OFF
+    batch = x_np.shape[0]
+    x = B.to_device(x_np, wl.dtype)
+    width = wl.d_model if wdev.get("wo") is not None else wl.n_heads * wl.head_dim
+    out = torch.full((batch, width), float("nan"), dtype=x.dtype, device="cuda")
+    nbytes = B.gta_workspace_bytes(cfg, B.GTA_MODE_DECODE, batch, 0, cache.k.shape[1], num_splits)
+    ws = B.alloc_workspace(nbytes)
+    sl = None if slots is None else torch.from_numpy(np.asarray(slots, dtype=np.int32)).cuda()
+    B.gta_decode(cfg, B.make_weights(wdev), x, batch, cache.struct, sl, out, num_splits, ws)
+    torch.cuda.synchronize()
+    return out
