@@ -463,8 +463,8 @@ int prefill_impl(const Dims &d, const gta_weights &w, const T *x, const int32_t 
 }
 
 template <typename T>
-int decode_impl(const Dims &d, const gta_weights &w, const T *x, int batch, const gta_cache &cache,
-                const int32_t *slots, T *out, const DecodeWs &ws, hipStream_t st) {
+void decode_project_impl(const Dims &d, const gta_weights &w, const T *x, int batch, const gta_cache &cache,
+                         const int32_t *slots, const DecodeWs &ws, hipStream_t st) {
   const T *wmat[4] = {(const T *)w.wq, (const T *)w.wk, (const T *)w.wc, (const T *)w.wg};
   const int wn[4] = {d.wq_w, d.wk_w, d.wc_w, d.wg_w};
   int off = 0;
@@ -473,9 +473,15 @@ int decode_impl(const Dims &d, const gta_weights &w, const T *x, int batch, cons
                 EpiStoreF32{ws.praw, d.wtot, off}, st);
     off += wn[i];
   }
-  CacheView cv = view_of(&cache, slots);
   finalize_decode_kernel<T><<<grid1d((int64_t)batch * d.wtot), 256, 0, st>>>(d, ws.praw, batch, ws.q, ws.g,
-                                                                            ws.oldlen, cv);
+                                                                            ws.oldlen, view_of(&cache, slots));
+}
+
+template <typename T>
+int decode_impl(const Dims &d, const gta_weights &w, const T *x, int batch, const gta_cache &cache,
+                const int32_t *slots, T *out, const DecodeWs &ws, hipStream_t st) {
+  decode_project_impl<T>(d, w, x, batch, cache, slots, ws, st);
+  CacheView cv = view_of(&cache, slots);
   dim3 agrid(ws.splits, d.nq, batch);
   attn_decode_generic_kernel<T><<<agrid, 64, d.dh * sizeof(float), st>>>(d, ws.q, ws.oldlen, cv, ws.splits, ws.part);
   decode_combine_kernel<<<dim3(d.nq, batch), 256, 0, st>>>(d, ws.part, ws.oldlen, ws.splits, ws.l);
@@ -526,6 +532,26 @@ int generic_decode(const Dims &d, const gta_weights &w, const void *x_new, int b
   if (d.dtype == GTA_BF16)
     return decode_impl<bf16>(d, w, (const bf16 *)x_new, batch, cache, slots, (bf16 *)out, ws, st);
   return decode_impl<float>(d, w, (const float *)x_new, batch, cache, slots, (float *)out, ws, st);
+}
+
+void generic_decode_project(const Dims &d, const gta_weights &w, const void *x_new, int batch,
+                            const gta_cache &cache, const int32_t *slots, const DecodeWs &ws, hipStream_t st) {
+  if (d.dtype == GTA_BF16) decode_project_impl<bf16>(d, w, (const bf16 *)x_new, batch, cache, slots, ws, st);
+  else decode_project_impl<float>(d, w, (const float *)x_new, batch, cache, slots, ws, st);
+}
+
+void launch_decode_commit(const gta_cache &cache, const int32_t *slots, const int32_t *oldlen, int batch,
+                          hipStream_t st) {
+  decode_commit_kernel<<<grid1d(batch), 256, 0, st>>>(view_of(&cache, slots), oldlen, batch);
+}
+
+void generic_out_proj_f32in(const Dims &d, const gta_weights &w, const float *O, int M, void *out, hipStream_t st) {
+  if (d.dtype == GTA_BF16)
+    launch_gemm(O, (int64_t)d.wg_w, 0, 1, (const bf16 *)w.wo, (int64_t)d.H, 0, M, d.H, d.wg_w, 1,
+                EpiStoreT<bf16>{(bf16 *)out, d.H}, st);
+  else
+    launch_gemm(O, (int64_t)d.wg_w, 0, 1, (const float *)w.wo, (int64_t)d.H, 0, M, d.H, d.wg_w, 1,
+                EpiStoreT<float>{(float *)out, d.H}, st);
 }
 
 int generic_cache_append(const Dims &d, const gta_cache &cache, const int32_t *slots, const void *k_new,

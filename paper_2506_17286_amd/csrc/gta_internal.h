@@ -66,7 +66,13 @@ int generic_cache_append(const Dims &d, const gta_cache &cache, const int32_t *s
                          const void *k_new, const void *c_new, const int32_t *cu_new, int batch,
                          int max_new, hipStream_t st);
 
-// Helper kernels reused by the tuned path.
+// Pieces of the generic path reused by the tuned path.
+void generic_decode_project(const Dims &d, const gta_weights &w, const void *x_new, int batch,
+                            const gta_cache &cache, const int32_t *slots, const DecodeWs &ws, hipStream_t st);
+void launch_decode_commit(const gta_cache &cache, const int32_t *slots, const int32_t *oldlen, int batch,
+                          hipStream_t st);
+void generic_out_proj_f32in(const Dims &d, const gta_weights &w, const float *O, int M, void *out, hipStream_t st);
+
 void launch_rowmap(const int32_t *cu, int batch, int64_t total, int32_t *seq_id, int32_t *pos,
                    hipStream_t st);
 void launch_rope_table(float2 *tab, int max_pos, int dh, double base, hipStream_t st);

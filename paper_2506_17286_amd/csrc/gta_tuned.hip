@@ -3,15 +3,9 @@
 namespace gta {
 
 bool tuned_prefill_supported(const Dims &) { return false; }
-bool tuned_decode_supported(const Dims &) { return false; }
 
 int tuned_prefill(const Dims &, const gta_weights &, const void *, const int32_t *, int, int64_t, int,
                   const gta_cache *, const int32_t *, void *, const PrefillWs &, hipStream_t) {
   return GTA_ERR_UNSUPPORTED;
 }
-int tuned_decode(const Dims &, const gta_weights &, const void *, int, const gta_cache &, const int32_t *, void *,
-                 const DecodeWs &, hipStream_t) {
-  return GTA_ERR_UNSUPPORTED;
-}
-
 }  // namespace gta

@@ -1,0 +1,126 @@
+"""GPU parity at the full sizes of the five benchmark workloads, in the launch configuration
+bench.py times.  Where the fp64 oracle cannot cover every output in seconds, it is run on whole
+sequences where that is cheap and on sampled query rows (first / last rows, tile boundaries +-1,
+random rows) elsewhere; the sample is stated in each test."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import gta_oracle as orc
+from paper_2506_17286_amd import binding as B
+from paper_2506_17286_amd import workloads as W
+
+import gpu_util as U
+
+pytestmark = pytest.mark.gpu
+
+
+def _sample_rows(T, rng, n_random=48):
+    rows = {0, 1, T - 1, T - 2}
+    for edge in (31, 32, 63, 64, 127, 128, 255, 256, 1023, 1024, T // 2):
+        for r in (edge - 1, edge, edge + 1):
+            if 0 <= r < T:
+                rows.add(r)
+    rows.update(int(r) for r in rng.integers(0, T, size=n_random))
+    return sorted(rows)
+
+
+def _check_prefill_workload(wl, full_seqs, sampled_seqs):
+    lens, cu, w, x = W.prefill_inputs(wl)
+    wdev = U.upload_weights(w, wl.dtype)
+    max_seq = int(lens.max())
+    cache = U.DeviceCache(wl, wl.batch, max_seq)
+    out = U.run_prefill(wl, wdev, x, cu if wl.min_seqlen is not None else None, batch=wl.batch, cache=cache,
+                        max_seqlen=max_seq)
+    cfg, wo = U.oracle_config(wl), U.oracle_weights(w)
+    rng = np.random.default_rng(wl.seed + 99)
+    assert np.array_equal(cache.seq_lens.cpu().numpy(), lens)
+    for b in sorted(set(full_seqs) | set(sampled_seqs)):
+        T = int(lens[b])
+        rows = None if b in full_seqs else _sample_rows(T, rng)
+        ref, Kref, Cref = orc.prefill_sequence(cfg, wo, x[cu[b]:cu[b + 1]], rows=rows)
+        got = U.f64(out[cu[b]:cu[b + 1]])
+        got = got if rows is None else got[rows]
+        ma, rr = U.assert_close(got, ref, wl.dtype, f"{wl.name} seq {b} ({'all' if rows is None else len(rows)} rows)")
+        U.assert_close(U.f64(cache.k[b, :T]), Kref, wl.dtype, f"{wl.name} K cache seq {b}")
+        U.assert_close(U.f64(cache.c[b, :T]), Cref, wl.dtype, f"{wl.name} C cache seq {b}")
+        print(f"{wl.name} seq {b} T={T}: max_abs {ma:.3e} rel_rms {rr:.3e}", flush=True)
+    assert torch.isfinite(out.float()).all()
+
+
+def test_config2_prefill_1b_bf16():
+    """B=4, T=4096, d_model 2048, 16 heads of 128, 4 maps, d_l 512, RoPE.  Oracle: every row of
+    sequence 0, sampled rows (~80 per sequence) of sequences 1-3; caches of all four."""
+    _check_prefill_workload(W.WORKLOADS[1], full_seqs=[0], sampled_seqs=[1, 2, 3])
+
+
+def _check_decode_workload(wl, check_seqs):
+    rng = W.make_rng(wl)
+    w = W.draw_weights(wl, rng)
+    x = W.draw_hidden(wl, rng, wl.batch)
+    wdev = U.upload_weights(w, wl.dtype)
+    max_seq = wl.seqlen + 1
+    k, c = W.make_decode_cache_device(wl, max_seq)
+    k0_last = k[:, wl.seqlen].clone()                 # noise in the row the step will overwrite
+    seq = torch.full((wl.batch,), wl.seqlen, dtype=torch.int32, device="cuda")
+    cache = U.DeviceCache(wl, wl.batch, max_seq, k=k, c=c, seq_lens=seq)
+    assert B.gta_uses_tuned_kernels(B.config_of(wl), B.GTA_MODE_DECODE) == 1
+    out = U.run_decode(wl, wdev, x, cache)
+    assert (cache.seq_lens == wl.seqlen + 1).all() and (cache.status == 0).all()
+    assert not torch.equal(k[:, wl.seqlen], k0_last)
+    cfg, wo = U.oracle_config(wl), U.oracle_weights(w)
+    got = U.f64(out)
+    for b in check_seqs:
+        kc = U.f64(k[b:b + 1]); cc = U.f64(c[b:b + 1])
+        kc[0, wl.seqlen] = np.nan; cc[0, wl.seqlen] = np.nan       # the oracle must write this row itself
+        sl = np.array([wl.seqlen], dtype=np.int32); st = np.zeros(1, dtype=np.int32)
+        ref = orc.decode(cfg, wo, x[b:b + 1], kc, cc, sl, st, [0])
+        ma, rr = U.assert_close(got[b:b + 1], ref, wl.dtype, f"{wl.name} seq {b}")
+        U.assert_close(U.f64(k[b, wl.seqlen]), kc[0, wl.seqlen], wl.dtype, "appended key row")
+        U.assert_close(U.f64(c[b, wl.seqlen]), cc[0, wl.seqlen], wl.dtype, "appended latent row")
+        print(f"{wl.name} seq {b}: max_abs {ma:.3e} rel_rms {rr:.3e}", flush=True)
+
+
+def test_config3_decode_b64_ctx8k_bf16():
+    """B=64, 8192 cached tokens each, 1 new token.  Oracle on 16 of the 64 sequences (every 4th)."""
+    _check_decode_workload(W.WORKLOADS[2], check_seqs=list(range(0, 64, 4)))
+
+
+def test_config4_decode_b8_ctx32k_bf16():
+    """B=8, 32768 cached tokens each, split-K.  Oracle on all 8 sequences."""
+    _check_decode_workload(W.WORKLOADS[3], check_seqs=list(range(8)))
+
+
+def test_config5_varlen_prefill_bf16():
+    """16 ragged sequences (lengths uniform in [512, 16384]), d_model 4096, 32 heads, 8 maps,
+    d_l 1024.  Oracle: every row of the shortest sequence; sampled rows of the longest and of one
+    other sequence."""
+    wl = W.WORKLOADS[4]
+    lens = W.draw_seqlens(wl, W.make_rng(wl))
+    order = np.argsort(lens)
+    _check_prefill_workload(wl, full_seqs=[int(order[0])], sampled_seqs=[int(order[-1]), int(order[7])])
+
+
+@pytest.mark.parametrize("shape", ["1b", "wide"])
+def test_tuned_decode_ragged_contexts(shape):
+    """The streaming decode kernels on ragged context lengths incl. 0, 1, block tails and empty
+    splits, every output element against the oracle."""
+    base = W.WORKLOADS[2] if shape == "1b" else W.scaled(W.WORKLOADS[4], kind="decode", min_seqlen=None)
+    ctx = [0, 1, 7, 8, 31, 32, 33, 255, 777, 1500]
+    wl = W.scaled(base, batch=len(ctx), seqlen=max(ctx))
+    assert B.gta_uses_tuned_kernels(B.config_of(wl), B.GTA_MODE_DECODE) == 1
+    for splits in (0, 1, 5, 64):
+        rng = W.make_rng(wl)
+        w = W.draw_weights(wl, rng, with_wo=(splits == 5))
+        x = W.draw_hidden(wl, rng, wl.batch)
+        max_seq = max(ctx) + 1
+        k_np, c_np = W.draw_cache(wl, rng, wl.batch, max_seq)
+        wdev = U.upload_weights(w, wl.dtype)
+        cache = U.DeviceCache(wl, wl.batch, max_seq, k=B.to_device(k_np, wl.dtype), c=B.to_device(c_np, wl.dtype),
+                              seq_lens=torch.tensor(ctx, dtype=torch.int32).cuda())
+        out = U.run_decode(wl, wdev, x, cache, num_splits=splits)
+        kc, cc = k_np.astype(np.float64), c_np.astype(np.float64)
+        sl = np.array(ctx, dtype=np.int32); st = np.zeros(len(ctx), dtype=np.int32)
+        ref = orc.decode(U.oracle_config(wl), U.oracle_weights(w), x, kc, cc, sl, st, list(range(len(ctx))))
+        U.assert_close(U.f64(out), ref, wl.dtype, f"tuned decode {shape} splits={splits}")
+        assert np.array_equal(cache.seq_lens.cpu().numpy(), sl)
