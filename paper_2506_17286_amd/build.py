@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libgta.so")
-SOURCES = ["gta_api.cpp", "gta_generic.hip", "gta_tuned.hip", "gta_decode_bf16.hip"]
+SOURCES = ["gta_api.cpp", "gta_generic.hip", "gta_tuned.hip", "gta_decode_bf16.hip", "gta_gemm_bf16.hip", "gta_prefill_bf16.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]

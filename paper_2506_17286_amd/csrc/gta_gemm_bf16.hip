@@ -1,0 +1,363 @@
+// bf16 MFMA GEMMs of the GTA pass for gfx950 (fp32 accumulation):
+//   * fused input projection  [Q | K | C | gate] = X . [W_Q | W_K | W_C | W_G]   (paper Sec. 3.2)
+//     with RoPE on q and k (App. B.1.1) and the cache write (App. B.1.3) in the epilogue,
+//   * value decoder  O_i = (L_{q(i)} W_{P,i}) * Sigmoid(gate)                     (Sec. 3.2),
+//   * plain output projection  U = O . W_O                                         (Sec. 3.3).
+//
+// All weights are row-major [in, out], i.e. the contraction index is the SLOW index of the weight
+// operand.  The kernel therefore computes the transposed tile D'[n][m] = sum_k W[k][n] X[m][k]:
+// the MFMA row operand comes from the weight tile through the LDS transpose read of gfx950
+// (ds_read_b64_tr_b16: each lane receives 4 consecutive k of one n), the MFMA column operand is
+// a plain 16-byte LDS read of an X row.  Each lane then owns 4 consecutive output columns of one
+// output row, which makes the RoPE pairing (j, j + d_h/2) lane-local and the stores 8 bytes wide.
+//
+// Workgroup tile BM x BN x BK with WGM x WGN waves of 32x32x16 MFMA tiles, global -> register ->
+// LDS staging with two LDS stages (one barrier per k-tile).
+#include <math.h>
+
+#include "gta_tuned.h"
+
+namespace gta {
+namespace {
+
+typedef __bf16 bf16;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(8))) short s16x8;
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+
+template <int BM_, int BN_, int BK_, int WGM_, int WGN_>
+struct GemmTile {
+  static constexpr int BM = BM_, BN = BN_, BK = BK_, WGM = WGM_, WGN = WGN_;
+  static constexpr int WM = BM / WGM, WN = BN / WGN, TM = WM / 32, TN = WN / 32;
+  static constexpr int NT = 64 * WGM * WGN;
+  static constexpr int A_PITCH = BK * 2 + 16;    // bytes per X row: 16 * odd -> conflict-free b128 reads
+  static constexpr int B_PITCH = BN * 2 + 64;    // bytes per weight k-row: == 64 mod 256 for the tr reads
+  static constexpr int A_BYTES = BM * A_PITCH, B_BYTES = BK * B_PITCH, STAGE = A_BYTES + B_BYTES;
+  static constexpr int SMEM = 2 * STAGE;
+  static_assert(WM % 32 == 0 && WN % 32 == 0 && BK % 16 == 0, "tile");
+};
+
+// acc[tn][tm][r]:  n = n_wave + tn*32 + 8*(r/4) + 4*(lane/32) + r%4,  m = m_wave + tm*32 + lane%32
+template <class T>
+__device__ __forceinline__ void gemm_mainloop(const bf16 *__restrict__ A, int64_t lda, int M, int m0,
+                                              const bf16 *__restrict__ B, int64_t ldb, int n0, int K, char *smem,
+                                              f32x16 (&acc)[T::TN][T::TM]) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wn = wave % T::WGN, wm = wave / T::WGN;
+  constexpr int A_CPR = T::BK / 8, A_RPP = T::NT / A_CPR, A_PASSES = T::BM / A_RPP;
+  constexpr int B_CPR = T::BN / 8, B_RPP = T::NT / B_CPR, B_PASSES = T::BK / B_RPP;
+  static_assert(T::BM % A_RPP == 0 && T::BK % B_RPP == 0 && A_PASSES >= 1 && B_PASSES >= 1, "staging");
+  const int a_c = tid % A_CPR, a_r = tid / A_CPR;
+  const int b_c = tid % B_CPR, b_r = tid / B_CPR;
+  u32x4 ra[A_PASSES], rb[B_PASSES];
+
+  auto gload = [&](int kt) {
+#pragma unroll
+    for (int i = 0; i < A_PASSES; ++i) {
+      const int row = min(m0 + a_r + i * A_RPP, M - 1);
+      ra[i] = *reinterpret_cast<const u32x4 *>(A + (int64_t)row * lda + kt * T::BK + a_c * 8);
+    }
+#pragma unroll
+    for (int i = 0; i < B_PASSES; ++i) {
+      const int krow = kt * T::BK + b_r + i * B_RPP;
+      rb[i] = *reinterpret_cast<const u32x4 *>(B + (int64_t)krow * ldb + n0 + b_c * 8);
+    }
+  };
+  auto sstore = [&](char *st) {
+#pragma unroll
+    for (int i = 0; i < A_PASSES; ++i)
+      *reinterpret_cast<u32x4 *>(st + (a_r + i * A_RPP) * T::A_PITCH + a_c * 16) = ra[i];
+#pragma unroll
+    for (int i = 0; i < B_PASSES; ++i)
+      *reinterpret_cast<u32x4 *>(st + T::A_BYTES + (b_r + i * B_RPP) * T::B_PITCH + b_c * 16) = rb[i];
+  };
+  // per-lane constant parts of the operand addresses
+  const int xoff = (wm * T::WM + (lane & 31)) * T::A_PITCH + (lane >> 5) * 16;
+  const int woff = T::A_BYTES + ((lane >> 5) * 8 + ((lane & 15) >> 2)) * T::B_PITCH +
+                   (wn * T::WN + ((lane >> 4) & 1) * 16 + (lane & 3) * 4) * 2;
+  auto compute = [&](const char *st) {
+#pragma unroll
+    for (int kk = 0; kk < T::BK / 16; ++kk) {
+      bf16x8 xf[T::TM];
+#pragma unroll
+      for (int tm = 0; tm < T::TM; ++tm)
+        xf[tm] = *reinterpret_cast<const bf16x8 *>(st + xoff + tm * 32 * T::A_PITCH + kk * 32);
+#pragma unroll
+      for (int tn = 0; tn < T::TN; ++tn) {
+        const char *wp = st + woff + kk * 16 * T::B_PITCH + tn * 64;
+        s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(wp));
+        s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(wp + 4 * T::B_PITCH));
+        s16x8 w8 = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        bf16x8 wf = __builtin_bit_cast(bf16x8, w8);
+#pragma unroll
+        for (int tm = 0; tm < T::TM; ++tm)
+          acc[tn][tm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, xf[tm], acc[tn][tm], 0, 0, 0);
+      }
+    }
+  };
+
+  const int nk = K / T::BK;
+  gload(0);
+  sstore(smem);
+  __syncthreads();
+  for (int kt = 0; kt < nk; ++kt) {
+    char *cur = smem + (kt & 1) * T::STAGE;
+    char *nxt = smem + ((kt & 1) ^ 1) * T::STAGE;
+    if (kt + 1 < nk) gload(kt + 1);
+    compute(cur);
+    if (kt + 1 < nk) sstore(nxt);
+    __syncthreads();
+  }
+}
+
+template <class T>
+__device__ __forceinline__ void zero_acc(f32x16 (&acc)[T::TN][T::TM]) {
+#pragma unroll
+  for (int tn = 0; tn < T::TN; ++tn)
+#pragma unroll
+    for (int tm = 0; tm < T::TM; ++tm)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[tn][tm][r] = 0.f;
+}
+
+__device__ __forceinline__ bf16x4 pack4(float a, float b, float c, float d) {
+  bf16x4 v;
+  v[0] = (bf16)a; v[1] = (bf16)b; v[2] = (bf16)c; v[3] = (bf16)d;
+  return v;
+}
+
+// Workgroup -> tile mapping.  Consecutive workgroup ids land on different XCDs (8 of them, each
+// with its own L2); the remap gives every XCD a contiguous range of tiles (n fastest) so the
+// workgroups that run together on one XCD share X strips and weight strips in its L2.
+__device__ __forceinline__ void tile_of_block(int ntn, int ntm, int &mt, int &nt) {
+  const int nblk = ntn * ntm;
+  int id = blockIdx.x;
+  const int per = nblk / 8;
+  if (id < per * 8) id = (id % 8) * per + id / 8;
+  mt = id / ntn;
+  nt = id % ntn;
+}
+
+// ------------------------------------------------------------------------------ projection
+constexpr int kHeadDim = 128;   // the RoPE epilogue is compiled for d_h = 128
+
+struct ProjArgs {
+  const bf16 *x; int64_t lda; int M, K;
+  const bf16 *w[4]; int width[4];     // W_Q, W_K, W_C, W_G and their output widths
+  bf16 *dst[4];                       // Q, K, C, gate pre-activation  [M, width]
+  const int32_t *seq_id, *pos;        // per packed token
+  const float2 *rope; int max_len;    // (cos, sin)[pos][j], NULL = no RoPE
+  int dh;
+  bf16 *kcache, *ccache; const int32_t *slots; int max_batch, max_seq;   // kcache NULL = no cache write
+};
+
+template <class T>
+__global__ __launch_bounds__(T::NT) void proj_gemm_kernel(ProjArgs a) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  const int wtot = a.width[0] + a.width[1] + a.width[2] + a.width[3];
+  int mt, nt;
+  tile_of_block(wtot / T::BN, (a.M + T::BM - 1) / T::BM, mt, nt);
+  int n_glob = nt * T::BN, seg = 0;
+  while (n_glob >= a.width[seg]) { n_glob -= a.width[seg]; ++seg; }   // widths are multiples of BN
+  const int m0 = mt * T::BM;
+  f32x16 acc[T::TN][T::TM];
+  zero_acc<T>(acc);
+  gemm_mainloop<T>(a.x, a.lda, a.M, m0, a.w[seg], a.width[seg], n_glob, a.K, smem, acc);
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wn = wave % T::WGN, wm = wave / T::WGN;
+  const int nw = n_glob + wn * T::WN;            // first column of this wave inside its segment
+  const int half = a.dh / 2;
+  const bool rotate = a.rope != nullptr && seg < 2;
+  bf16 *cache = seg == 1 ? a.kcache : (seg == 2 ? a.ccache : nullptr);
+  const int width = a.width[seg];
+#pragma unroll
+  for (int tm = 0; tm < T::TM; ++tm) {
+    const int m = m0 + wm * T::WM + tm * 32 + (lane & 31);
+    if (m >= a.M) continue;
+    const int p = a.pos[m];
+    if (rotate && p < a.max_len) {
+      // wave tile spans whole heads (WN % d_h == 0); pair column j with j + d_h/2 of the same head
+      constexpr int tiles_half = kHeadDim / 64, tiles_head = kHeadDim / 32;
+#pragma unroll
+      for (int tn = 0; tn < T::TN; ++tn) {
+        if ((tn % tiles_head) >= tiles_half) continue;
+        const int tn_hi = tn + tiles_half;
+        if (tn_hi >= T::TN) continue;
+#pragma unroll
+        for (int rq = 0; rq < 4; ++rq) {
+          const int j = (tn % tiles_head) * 32 + rq * 8 + (lane >> 5) * 4;
+          const float4 *tp = reinterpret_cast<const float4 *>(a.rope + (int64_t)p * half + j);
+          const float4 t0 = tp[0], t1 = tp[1];
+          const float cs[4] = {t0.x, t0.z, t1.x, t1.z}, sn[4] = {t0.y, t0.w, t1.y, t1.w};
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const float lo = acc[tn][tm][rq * 4 + i], hi = acc[tn_hi][tm][rq * 4 + i];
+            acc[tn][tm][rq * 4 + i] = lo * cs[i] - hi * sn[i];
+            acc[tn_hi][tm][rq * 4 + i] = hi * cs[i] + lo * sn[i];
+          }
+        }
+      }
+    }
+    bf16 *drow = a.dst[seg] + (int64_t)m * width + nw;
+    bf16 *crow = nullptr;
+    if (cache) {
+      const int b = a.seq_id[m];
+      const int slot = a.slots ? a.slots[b] : b;
+      if (slot >= 0 && slot < a.max_batch && p < a.max_seq) crow = cache + ((int64_t)slot * a.max_seq + p) * width + nw;
+    }
+#pragma unroll
+    for (int tn = 0; tn < T::TN; ++tn)
+#pragma unroll
+      for (int rq = 0; rq < 4; ++rq) {
+        const int n = tn * 32 + rq * 8 + (lane >> 5) * 4;
+        const bf16x4 v = pack4(acc[tn][tm][rq * 4], acc[tn][tm][rq * 4 + 1], acc[tn][tm][rq * 4 + 2], acc[tn][tm][rq * 4 + 3]);
+        *reinterpret_cast<bf16x4 *>(drow + n) = v;
+        if (crow) *reinterpret_cast<bf16x4 *>(crow + n) = v;
+      }
+  }
+}
+
+// ------------------------------------------------------------------------------ value decoder
+struct DecoderArgs {
+  const bf16 *L; int64_t ldl; int M;          // [M, n_q*d_l] normalised group outputs
+  const bf16 *wp; int dl, dh, hpq, nh;        // [n_h, d_l, d_h]
+  const bf16 *g; int gate;                    // [M, n_h*d_h] gate pre-activation
+  bf16 *out;                                  // [M, n_h*d_h]
+};
+
+template <class T>
+__global__ __launch_bounds__(T::NT) void decoder_gemm_kernel(DecoderArgs a) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  const int tiles_per_head = a.dh / T::BN;     // BN divides d_h
+  int mt, nt;
+  tile_of_block(a.nh * tiles_per_head, (a.M + T::BM - 1) / T::BM, mt, nt);
+  const int head = nt / tiles_per_head, n_in_head = (nt % tiles_per_head) * T::BN;
+  const int m0 = mt * T::BM;
+  f32x16 acc[T::TN][T::TM];
+  zero_acc<T>(acc);
+  gemm_mainloop<T>(a.L + (head / a.hpq) * a.dl, a.ldl, a.M, m0, a.wp + (int64_t)head * a.dl * a.dh, a.dh, n_in_head,
+                   a.dl, smem, acc);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wn = wave % T::WGN, wm = wave / T::WGN;
+  const int64_t ldo = (int64_t)a.nh * a.dh;
+  const int col0 = head * a.dh + n_in_head + wn * T::WN;
+#pragma unroll
+  for (int tm = 0; tm < T::TM; ++tm) {
+    const int m = m0 + wm * T::WM + tm * 32 + (lane & 31);
+    if (m >= a.M) continue;
+#pragma unroll
+    for (int tn = 0; tn < T::TN; ++tn)
+#pragma unroll
+      for (int rq = 0; rq < 4; ++rq) {
+        const int64_t o = (int64_t)m * ldo + col0 + tn * 32 + rq * 8 + (lane >> 5) * 4;
+        float v[4] = {acc[tn][tm][rq * 4], acc[tn][tm][rq * 4 + 1], acc[tn][tm][rq * 4 + 2], acc[tn][tm][rq * 4 + 3]};
+        if (a.gate) {
+          const bf16x4 gz = *reinterpret_cast<const bf16x4 *>(a.g + o);
+#pragma unroll
+          for (int i = 0; i < 4; ++i) v[i] *= 1.0f / (1.0f + __expf(-(float)gz[i]));
+        }
+        *reinterpret_cast<bf16x4 *>(a.out + o) = pack4(v[0], v[1], v[2], v[3]);
+      }
+  }
+}
+
+// ------------------------------------------------------------------------------ plain GEMM
+struct PlainArgs { const bf16 *A; int64_t lda; int M, N, K; const bf16 *B; bf16 *C; };
+
+template <class T>
+__global__ __launch_bounds__(T::NT) void plain_gemm_kernel(PlainArgs a) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  int mt, nt;
+  tile_of_block(a.N / T::BN, (a.M + T::BM - 1) / T::BM, mt, nt);
+  const int m0 = mt * T::BM, n0 = nt * T::BN;
+  f32x16 acc[T::TN][T::TM];
+  zero_acc<T>(acc);
+  gemm_mainloop<T>(a.A, a.lda, a.M, m0, a.B, a.N, n0, a.K, smem, acc);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wn = wave % T::WGN, wm = wave / T::WGN;
+#pragma unroll
+  for (int tm = 0; tm < T::TM; ++tm) {
+    const int m = m0 + wm * T::WM + tm * 32 + (lane & 31);
+    if (m >= a.M) continue;
+#pragma unroll
+    for (int tn = 0; tn < T::TN; ++tn)
+#pragma unroll
+      for (int rq = 0; rq < 4; ++rq) {
+        const int n = n0 + wn * T::WN + tn * 32 + rq * 8 + (lane >> 5) * 4;
+        *reinterpret_cast<bf16x4 *>(a.C + (int64_t)m * a.N + n) =
+            pack4(acc[tn][tm][rq * 4], acc[tn][tm][rq * 4 + 1], acc[tn][tm][rq * 4 + 2], acc[tn][tm][rq * 4 + 3]);
+      }
+  }
+}
+
+typedef GemmTile<256, 256, 64, 2, 2> TileBig;    // wave tile 128 x 128
+typedef GemmTile<256, 128, 64, 4, 1> TileHead;   // one 128-wide head per workgroup, wave tile 64(m) x 128(n)
+
+template <class T, class K, class Args>
+void launch(K kernel, const Args &a, int ntiles, hipStream_t st) {
+  static bool attr_set = false;
+  if (!attr_set) {
+    (void)hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, T::SMEM);
+    attr_set = true;
+  }
+  kernel<<<ntiles, T::NT, T::SMEM, st>>>(a);
+}
+
+}  // namespace
+
+bool gemm_shapes_supported(const Dims &d) {
+  // RoPE pairing is lane-local only if a wave tile (128 columns) holds whole heads
+  if (d.dtype != GTA_BF16 || d.dh != 128) return false;
+  if (d.H % 64 || d.dl % 64 || d.wq_w % 128 || d.wk_w % 128 || d.wc_w % 128 || d.wg_w % 128) return false;
+  return true;
+}
+
+void launch_proj_gemm(const Dims &d, const gta_weights &w, const void *x, int M, const PrefillWs &ws,
+                      const gta_cache *cache, const int32_t *slots, int max_len, hipStream_t st) {
+  ProjArgs a{};
+  a.x = (const bf16 *)x; a.lda = d.H; a.M = M; a.K = d.H;
+  const void *wm[4] = {w.wq, w.wk, w.wc, w.wg};
+  const int wd[4] = {d.wq_w, d.wk_w, d.wc_w, d.wg_w};
+  void *dst[4] = {ws.q, ws.k, ws.c, ws.g};
+  bool big = true;
+  for (int i = 0; i < 4; ++i) {
+    a.w[i] = (const bf16 *)wm[i]; a.width[i] = wd[i]; a.dst[i] = (bf16 *)dst[i];
+    if (wd[i] % 256) big = false;
+  }
+  a.seq_id = ws.seq_id; a.pos = ws.pos;
+  a.rope = d.rope ? ws.rope : nullptr; a.max_len = max_len; a.dh = d.dh;
+  if (cache) {
+    a.kcache = (bf16 *)cache->k; a.ccache = (bf16 *)cache->c; a.slots = slots;
+    a.max_batch = cache->max_batch; a.max_seq = cache->max_seq;
+  }
+  if (big) {
+    const int nt = (d.wtot / 256) * ((M + 255) / 256);
+    launch<TileBig>(proj_gemm_kernel<TileBig>, a, nt, st);
+  } else {
+    const int nt = (d.wtot / 128) * ((M + 255) / 256);
+    launch<TileHead>(proj_gemm_kernel<TileHead>, a, nt, st);
+  }
+}
+
+void launch_decoder_gemm(const Dims &d, const void *L, const void *wp, const void *g, void *out, int M,
+                         hipStream_t st) {
+  DecoderArgs a{};
+  a.L = (const bf16 *)L; a.ldl = (int64_t)d.nq * d.dl; a.M = M;
+  a.wp = (const bf16 *)wp; a.dl = d.dl; a.dh = d.dh; a.hpq = d.hpq; a.nh = d.nh;
+  a.g = (const bf16 *)g; a.gate = d.gate; a.out = (bf16 *)out;
+  const int nt = d.nh * (d.dh / 128) * ((M + 255) / 256);
+  launch<TileHead>(decoder_gemm_kernel<TileHead>, a, nt, st);
+}
+
+void launch_plain_gemm(const void *A, int64_t lda, int M, int N, int K, const void *B, void *C, hipStream_t st) {
+  PlainArgs a{(const bf16 *)A, lda, M, N, K, (const bf16 *)B, (bf16 *)C};
+  if (N % 256 == 0) launch<TileBig>(plain_gemm_kernel<TileBig>, a, (N / 256) * ((M + 255) / 256), st);
+  else launch<TileHead>(plain_gemm_kernel<TileHead>, a, (N / 128) * ((M + 255) / 256), st);
+}
+
+}  // namespace gta

@@ -276,10 +276,10 @@ __device__ void wave_attend(const float *qw, const T *Kb, int64_t kstride, const
 
 constexpr int kNAcc = 16;  // 64 lanes x 16 = 1024 latent columns per pass
 
-template <typename T>
+template <typename T, typename TL>
 __global__ __launch_bounds__(256) void attn_prefill_generic_kernel(Dims d, const T *Q, const T *K, const T *C,
                                                                    const int32_t *cu, int per_seq, int max_len,
-                                                                   float *L) {
+                                                                   TL *L) {
   extern __shared__ float qs[];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int b = blockIdx.z, g = blockIdx.y;
@@ -298,11 +298,11 @@ __global__ __launch_bounds__(256) void attn_prefill_generic_kernel(Dims d, const
     float m = -INFINITY, l = 0.f, acc[kNAcc] = {};
     wave_attend<T, kNAcc>(qw, Kb, d.wk_w, Cb, d.wc_w, 0, t + 1, d.dh, c0, d.dl, lane, m, l, acc);
     const float inv = 1.0f / l;
-    float *Lr = L + (start + t) * (int64_t)(d.nq * d.dl) + g * d.dl + c0;
+    TL *Lr = L + (start + t) * (int64_t)(d.nq * d.dl) + g * d.dl + c0;
 #pragma unroll
     for (int i = 0; i < kNAcc; ++i) {
       int col = lane + 64 * i;
-      if (c0 + col < d.dl) Lr[col] = acc[i] * inv;
+      if (c0 + col < d.dl) stf(Lr, col, acc[i] * inv);
     }
   }
 }
@@ -445,7 +445,7 @@ int prefill_impl(const Dims &d, const gta_weights &w, const T *x, const int32_t 
   if (cache) launch_prefill_commit(*cache, slots, cu, batch, total, st);
   // shared attention map x latent values, one map per group (Sec. 3.3)
   dim3 agrid((max_len + 3) / 4, d.nq, batch);
-  attn_prefill_generic_kernel<T><<<agrid, 256, 4 * d.dh * sizeof(float), st>>>(
+  attn_prefill_generic_kernel<T, float><<<agrid, 256, 4 * d.dh * sizeof(float), st>>>(
       d, (const T *)ws.q, (const T *)ws.k, (const T *)ws.c, cu, per_seq, max_len, (float *)ws.l);
   // value decoder with gate epilogue (Sec. 3.2), then the optional output projection (Sec. 3.3)
   const float *L = (const float *)ws.l;
@@ -538,6 +538,13 @@ void generic_decode_project(const Dims &d, const gta_weights &w, const void *x_n
                             const gta_cache &cache, const int32_t *slots, const DecodeWs &ws, hipStream_t st) {
   if (d.dtype == GTA_BF16) decode_project_impl<bf16>(d, w, (const bf16 *)x_new, batch, cache, slots, ws, st);
   else decode_project_impl<float>(d, w, (const float *)x_new, batch, cache, slots, ws, st);
+}
+
+void launch_attn_prefill_rowwise_bf16(const Dims &d, const void *q, const void *k, const void *c, const int32_t *cu,
+                                      int batch, int64_t total, int max_len, void *L, hipStream_t st) {
+  dim3 agrid((max_len + 3) / 4, d.nq, batch);
+  attn_prefill_generic_kernel<bf16, bf16><<<agrid, 256, 4 * d.dh * sizeof(float), st>>>(
+      d, (const bf16 *)q, (const bf16 *)k, (const bf16 *)c, cu, (int)(total / batch), max_len, (bf16 *)L);
 }
 
 void launch_decode_commit(const gta_cache &cache, const int32_t *slots, const int32_t *oldlen, int batch,

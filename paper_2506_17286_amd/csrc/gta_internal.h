@@ -73,6 +73,8 @@ void launch_decode_commit(const gta_cache &cache, const int32_t *slots, const in
                           hipStream_t st);
 void generic_out_proj_f32in(const Dims &d, const gta_weights &w, const float *O, int M, void *out, hipStream_t st);
 
+void launch_attn_prefill_rowwise_bf16(const Dims &d, const void *q, const void *k, const void *c, const int32_t *cu,
+                                      int batch, int64_t total, int max_len, void *L, hipStream_t st);
 void launch_rowmap(const int32_t *cu, int batch, int64_t total, int32_t *seq_id, int32_t *pos,
                    hipStream_t st);
 void launch_rope_table(float2 *tab, int max_pos, int dh, double base, hipStream_t st);

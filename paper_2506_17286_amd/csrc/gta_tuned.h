@@ -13,4 +13,17 @@ int tuned_prefill(const Dims &d, const gta_weights &w, const void *x, const int3
 int tuned_decode(const Dims &d, const gta_weights &w, const void *x_new, int batch, const gta_cache &cache,
                  const int32_t *slots, void *out, const DecodeWs &ws, hipStream_t st);
 
+// bf16 MFMA GEMMs (gta_gemm_bf16.hip)
+bool gemm_shapes_supported(const Dims &d);
+void launch_proj_gemm(const Dims &d, const gta_weights &w, const void *x, int M, const PrefillWs &ws,
+                      const gta_cache *cache, const int32_t *slots, int max_len, hipStream_t st);
+void launch_decoder_gemm(const Dims &d, const void *L, const void *wp, const void *g, void *out, int M,
+                         hipStream_t st);
+void launch_plain_gemm(const void *A, int64_t lda, int M, int N, int K, const void *B, void *C, hipStream_t st);
+
+// bf16 MFMA causal prefill attention (gta_prefill_bf16.hip)
+bool attn_prefill_supported(const Dims &d);
+void launch_attn_prefill_bf16(const Dims &d, const void *q, const void *k, const void *c, const int32_t *cu,
+                              int batch, int64_t total, int max_len, void *L, hipStream_t st);
+
 }  // namespace gta

@@ -1,11 +1,30 @@
+// Orchestration of the tuned bf16 prefill: which kernels run, in which order, on which buffers.
 #include "gta_tuned.h"
 
 namespace gta {
 
-bool tuned_prefill_supported(const Dims &) { return false; }
+bool tuned_prefill_supported(const Dims &d) { return gemm_shapes_supported(d); }
 
-int tuned_prefill(const Dims &, const gta_weights &, const void *, const int32_t *, int, int64_t, int,
-                  const gta_cache *, const int32_t *, void *, const PrefillWs &, hipStream_t) {
-  return GTA_ERR_UNSUPPORTED;
+int tuned_prefill(const Dims &d, const gta_weights &w, const void *x, const int32_t *cu, int batch, int64_t total,
+                  int max_len, const gta_cache *cache, const int32_t *slots, void *out, const PrefillWs &ws,
+                  hipStream_t st) {
+  const int M = (int)total;
+  launch_rowmap(cu, batch, total, ws.seq_id, ws.pos, st);
+  if (d.rope) launch_rope_table(ws.rope, max_len, d.dh, d.rope_base, st);
+  // Sec. 3.2 projections + App. B.1.1 RoPE + cache write, one MFMA GEMM
+  launch_proj_gemm(d, w, x, M, ws, cache, slots, max_len, st);
+  if (cache) launch_prefill_commit(*cache, slots, cu, batch, total, st);
+  // Sec. 3.3: one causal softmax map per group applied to the latent values
+  if (attn_prefill_supported(d)) launch_attn_prefill_bf16(d, ws.q, ws.k, ws.c, cu, batch, total, max_len, ws.l, st);
+  else launch_attn_prefill_rowwise_bf16(d, ws.q, ws.k, ws.c, cu, batch, total, max_len, ws.l, st);
+  // Sec. 3.2 value decoder with the gate in the epilogue, then the optional W_O
+  if (w.wo) {
+    launch_decoder_gemm(d, ws.l, w.wp, ws.g, ws.o, M, st);
+    launch_plain_gemm(ws.o, d.wg_w, M, d.H, d.wg_w, w.wo, out, st);
+  } else {
+    launch_decoder_gemm(d, ws.l, w.wp, ws.g, out, M, st);
+  }
+  return check_launch();
 }
+
 }  // namespace gta

@@ -124,3 +124,30 @@ def test_tuned_decode_ragged_contexts(shape):
         ref = orc.decode(U.oracle_config(wl), U.oracle_weights(w), x, kc, cc, sl, st, list(range(len(ctx))))
         U.assert_close(U.f64(out), ref, wl.dtype, f"tuned decode {shape} splits={splits}")
         assert np.array_equal(cache.seq_lens.cpu().numpy(), sl)
+
+
+@pytest.mark.parametrize("shape,with_wo", [("1b", False), ("1b", True), ("wide", False)])
+def test_tuned_prefill_ragged_small(shape, with_wo):
+    """The MFMA prefill path (1B and wide shapes) on short ragged sequences spanning several tiles
+    and tails, every output element and every cached row against the oracle."""
+    base = W.WORKLOADS[1] if shape == "1b" else W.WORKLOADS[4]
+    lens = [1, 37, 256, 300, 129, 64]
+    wl = W.scaled(base, batch=len(lens), seqlen=max(lens), min_seqlen=None)
+    assert B.gta_uses_tuned_kernels(B.config_of(wl), B.GTA_MODE_PREFILL) == 1
+    rng = W.make_rng(wl)
+    w = W.draw_weights(wl, rng, with_wo=with_wo)
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    x = W.draw_hidden(wl, rng, int(cu[-1]))
+    wdev = U.upload_weights(w, wl.dtype)
+    slots = [5, 0, 3, 1, 6, 2]
+    cache = U.DeviceCache(wl, 7, 320, fill=-3.0)
+    out = U.run_prefill(wl, wdev, x, cu, cache=cache, slots=slots)
+    ref, Kref, Cref = orc.prefill(U.oracle_config(wl), U.oracle_weights(w), x, cu)
+    U.assert_close(U.f64(out), ref, wl.dtype, f"tuned prefill {shape}")
+    kc, cc = U.f64(cache.k), U.f64(cache.c)
+    for b, s in enumerate(slots):
+        U.assert_close(kc[s, :lens[b]], Kref[cu[b]:cu[b + 1]], wl.dtype, "K cache")
+        U.assert_close(cc[s, :lens[b]], Cref[cu[b]:cu[b + 1]], wl.dtype, "C cache")
+        assert np.all(kc[s, lens[b]:] == -3.0) and np.all(cc[s, lens[b]:] == -3.0)
+        assert int(cache.seq_lens[s]) == lens[b]
+    assert np.all(kc[4] == -3.0) and int(cache.seq_lens[4]) == 0
