@@ -1,0 +1,268 @@
+#!/usr/bin/env python3
+"""Benchmark of the GTA attention pass on ONE MI355X: prints one JSON line.
+
+The headline metric names two things, so both are measured in every run:
+  * decode at 32K context (B=8, 32768 cached tokens, split-K): cache bytes streamed per second
+    over the WHOLE gta_decode step and microseconds per generated token -- the line's `value`;
+  * causal prefill of the 1B-class workload (B=4, T=4096, bf16): TFLOP/s of the whole
+    gta_prefill call and fraction of the bf16 MFMA peak -- under the key "prefill".
+The batched decode workload (B=64, 8192 cached tokens) is reported under "decode_b64_8k".
+
+A "step" is one library call (gta_decode or gta_prefill) on inputs already resident in HBM.
+`roofline` objects are for the dominant kernel of each path, timed live with HIP events around
+the stage entry point that launches exactly that kernel in the same configuration.
+`cpu_baseline` is the fp64 oracle timed on the host cores of this machine on a stated sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_HBM_GBPS = 8000.0        # MI355X HBM3E
+
+
+def _sync():
+    import torch
+    torch.cuda.synchronize()
+
+
+def _time_steps(fn, steps, warmup):
+    for i in range(warmup):
+        fn(i)
+    _sync()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        fn(warmup + i)
+    _sync()
+    return (time.perf_counter() - t0) / steps
+
+
+def _event_time(fn, reps):
+    """Average duration in seconds of fn() measured with HIP events on the current stream."""
+    import torch
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+    fn()
+    _sync()
+    for a, b in evs:
+        a.record(); fn(); b.record()
+    _sync()
+    return sum(a.elapsed_time(b) for a, b in evs) / reps * 1e-3
+
+
+def bench_decode(wl, steps, warmup, want_cpu_baseline):
+    import numpy as np
+    import torch
+    from paper_2506_17286_amd import binding as B, workloads as W, costmodel as cm
+
+    cfg = B.config_of(wl)
+    rng = W.make_rng(wl)
+    w = W.draw_weights(wl, rng)
+    x_np = W.draw_hidden(wl, rng, wl.batch)
+    wdev = {k: B.to_device(v, wl.dtype) for k, v in w.items()}
+    gw = B.make_weights(wdev)
+    x = B.to_device(x_np, wl.dtype)
+    max_seq = wl.seqlen + steps + warmup + 8
+    # two distinct cache allocations, alternated, so no step can be served from the Infinity Cache
+    caches = []
+    for salt in range(2):
+        k, c = W.make_decode_cache_device(wl, max_seq, salt=salt)
+        seq = torch.full((wl.batch,), wl.seqlen, dtype=torch.int32, device="cuda")
+        st = torch.zeros(wl.batch, dtype=torch.int32, device="cuda")
+        caches.append((k, c, seq, st, B.make_cache(k, c, seq, st)))
+    out = torch.empty((wl.batch, wl.n_heads * wl.head_dim), dtype=x.dtype, device="cuda")
+    ws = B.alloc_workspace(B.gta_workspace_bytes(cfg, B.GTA_MODE_DECODE, wl.batch, 0, max_seq, 0))
+
+    def step(i):
+        B.gta_decode(cfg, gw, x, wl.batch, caches[i % 2][4], None, out, 0, ws)
+
+    sec = _time_steps(step, steps, warmup)
+    assert all(int(c[3].abs().sum()) == 0 for c in caches), "a cache slot overflowed"
+    # context actually streamed in the timed steps: both caches advanced one row per call on them
+    ctx = wl.seqlen + (warmup + steps) // 2
+    cache_bytes = cm.decode_cache_bytes(wl, [ctx] * wl.batch)
+    res = {
+        "workload": wl.name, "us_per_step": sec * 1e6, "us_per_token": sec * 1e6 / wl.batch,
+        "tokens_per_s": wl.batch / sec, "cache_GBps": cache_bytes / sec / 1e9,
+        "frac_hbm_peak_whole_step": cache_bytes / sec / 1e9 / PEAK_HBM_GBPS,
+    }
+    # dominant kernel: the split-K streaming attention kernel alone (stage entry point)
+    q32 = torch.randn((wl.batch, wl.n_qgroups * wl.head_dim), device="cuda", dtype=torch.float32) * 0.9
+    flip = [0]
+
+    def attn_only():
+        flip[0] ^= 1
+        B.gta_decode_attention(cfg, q32, caches[flip[0]][4], None, wl.batch, 0, ws)
+
+    ksec = _event_time(attn_only, max(steps, 10))
+    kbytes = cm.decode_cache_bytes(wl, [int(caches[0][2][0])] * wl.batch)
+    res["roofline"] = {"kernel": "decode_attn_kernel", "bound": "hbm", "achieved": kbytes / ksec / 1e9,
+                       "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": kbytes / ksec / 1e9 / PEAK_HBM_GBPS,
+                       "traffic": None, "us_per_launch": ksec * 1e6, "algorithmic_bytes_per_launch": kbytes}
+    if want_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline_decode(wl, w, x_np, caches[0])
+    return res
+
+
+def bench_prefill(wl, steps, warmup, want_cpu_baseline):
+    import numpy as np
+    import torch
+    from paper_2506_17286_amd import binding as B, workloads as W, costmodel as cm
+
+    cfg = B.config_of(wl)
+    lens, cu, w, x_np = W.prefill_inputs(wl)
+    total = int(cu[-1])
+    wdev = {k: B.to_device(v, wl.dtype) for k, v in w.items()}
+    gw = B.make_weights(wdev)
+    x = B.to_device(x_np, wl.dtype)
+    max_seq = int(lens.max())
+    kw, cw = wl.kv_width
+    k = torch.zeros((wl.batch, max_seq, kw), dtype=x.dtype, device="cuda")
+    c = torch.zeros((wl.batch, max_seq, cw), dtype=x.dtype, device="cuda")
+    seq = torch.zeros(wl.batch, dtype=torch.int32, device="cuda")
+    st = torch.zeros(wl.batch, dtype=torch.int32, device="cuda")
+    cache = B.make_cache(k, c, seq, st)
+    cud = torch.from_numpy(cu).cuda() if wl.min_seqlen is not None else None
+    out = torch.empty((total, wl.n_heads * wl.head_dim), dtype=x.dtype, device="cuda")
+    ws = B.alloc_workspace(B.gta_workspace_bytes(cfg, B.GTA_MODE_PREFILL, wl.batch, total, max_seq))
+
+    def step(i):
+        B.gta_prefill(cfg, gw, x, cud, wl.batch, total, max_seq, cache, None, out, ws)
+
+    sec = _time_steps(step, steps, warmup)
+    fl = cm.prefill_flops(wl, lens)
+    res = {
+        "workload": wl.name, "ms_per_step": sec * 1e3, "tokens_per_s": total / sec,
+        "tflops": fl["total"] / sec / 1e12, "frac_mfma_peak_whole_call": fl["total"] / sec / 1e12 / PEAK_BF16_TFLOPS,
+        "algorithmic_flops": fl,
+    }
+    # dominant kernel: the causal attention kernel alone (stage entry point), q/k/c of the
+    # shapes and scale the projection produces
+    qd = (torch.randn((total, wl.n_qgroups * wl.head_dim), device="cuda") * 0.9).to(x.dtype)
+    kd = (torch.randn((total, kw), device="cuda") * 0.9).to(x.dtype)
+    cd = (torch.randn((total, cw), device="cuda") * 0.9).to(x.dtype)
+    ld = torch.empty((total, wl.n_qgroups * wl.latent_dim), dtype=x.dtype, device="cuda")
+
+    def attn_only():
+        B.gta_prefill_attention(cfg, qd, kd, cd, cud, wl.batch, total, max_seq, ld)
+
+    ksec = _event_time(attn_only, max(steps, 10))
+    res["roofline"] = {"kernel": "attn_prefill_kernel", "bound": "mfma", "achieved": fl["attn"] / ksec / 1e12,
+                       "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": fl["attn"] / ksec / 1e12 / PEAK_BF16_TFLOPS,
+                       "traffic": None, "us_per_launch": ksec * 1e6, "algorithmic_flops_per_launch": fl["attn"]}
+    if want_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline_prefill(wl, w, x_np, lens, cu)
+    return res
+
+
+def _blas_threads():
+    try:
+        from threadpoolctl import threadpool_info
+        n = [p.get("num_threads", 1) for p in threadpool_info() if p.get("user_api") == "blas"]
+        return max(n) if n else 1
+    except Exception:
+        return 1
+
+
+def cpu_baseline_decode(wl, w, x_np, cache0):
+    """The oracle's decode step on the same workload (all sequences), host cores of this machine."""
+    import numpy as np
+    import torch
+    from oracle import gta_oracle as orc
+    from paper_2506_17286_amd import costmodel as cm
+    cfg = orc.OracleConfig(wl.d_model, wl.n_heads, wl.n_qgroups, wl.n_kgroups, wl.n_cgroups, wl.head_dim,
+                           wl.latent_dim, rope=wl.rope, rope_base=wl.rope_base)
+    ow = orc.OracleWeights(w["wq"], w["wk"], w["wc"], w["wg"], w["wp"]).f64()
+    k, c, seq = cache0[0], cache0[1], cache0[2]
+    nseq = min(wl.batch, 8)
+    t = 0.0
+    rows = 0
+    for b in range(nseq):
+        n = int(seq[b])
+        kc = k[b:b + 1, :n + 1].to(torch.float64).cpu().numpy()
+        cc = c[b:b + 1, :n + 1].to(torch.float64).cpu().numpy()
+        sl = np.array([n], dtype=np.int32); stt = np.zeros(1, dtype=np.int32)
+        t0 = time.perf_counter()
+        orc.decode(cfg, ow, x_np[b:b + 1], kc, cc, sl, stt, [0])
+        t += time.perf_counter() - t0
+        rows += n + 1
+    by = cm.decode_cache_bytes(wl, [rows])
+    return {"value": by / t / 1e9, "unit": "GB/s", "cores": _blas_threads(), "kind": "oracle",
+            "sample": f"oracle decode step of {nseq} of {wl.batch} sequences ({rows} cached rows, fp64 copies "
+                      f"of the same cache; bytes counted at the bf16 cache size), {t:.2f} s"}
+
+
+def cpu_baseline_prefill(wl, w, x_np, lens, cu):
+    import numpy as np
+    from oracle import gta_oracle as orc
+    from paper_2506_17286_amd import costmodel as cm
+    cfg = orc.OracleConfig(wl.d_model, wl.n_heads, wl.n_qgroups, wl.n_kgroups, wl.n_cgroups, wl.head_dim,
+                           wl.latent_dim, rope=wl.rope, rope_base=wl.rope_base)
+    ow = orc.OracleWeights(w["wq"], w["wk"], w["wc"], w["wg"], w["wp"]).f64()
+    T = int(lens[0])
+    t0 = time.perf_counter()
+    orc.prefill_sequence(cfg, ow, x_np[cu[0]:cu[1]])
+    t = time.perf_counter() - t0
+    fl = cm.prefill_flops(wl, [T])["total"]
+    return {"value": fl / t / 1e12, "unit": "TFLOP/s", "cores": _blas_threads(), "kind": "oracle",
+            "sample": f"oracle prefill of sequence 0 of {wl.batch} (T={T}, every row; algorithmic flops of that "
+                      f"sequence / wall time), {t:.2f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--only", choices=["decode32k", "decode8k", "prefill"], default=None,
+                    help="measure one workload only (profiling runs)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no collectives, no sharding): use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2506_17286_amd import binding as B, workloads as W
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    B.load()   # fails loudly if the HIP library is not built
+    torch.cuda.set_device(0)
+    cpu = not args.no_cpu_baseline
+    dec = pre = dec8 = None
+    if args.only in (None, "decode32k"):
+        dec = bench_decode(W.by_name("decode_b8_32k_bf16"), args.steps, args.warmup, cpu)
+    if args.only in (None, "prefill"):
+        pre = bench_prefill(W.by_name("prefill_1b_bf16"), args.steps, args.warmup, cpu)
+    if args.only in (None, "decode8k"):
+        dec8 = bench_decode(W.by_name("decode_b64_8k_bf16"), args.steps, args.warmup, False)
+    main_res = dec or pre or dec8
+    line = {
+        "metric": "GTA decode HBM GB/s & us/token @32K ctx; prefill bf16 TFLOP/s (% of peak)",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+    }
+    if main_res is dec or main_res is dec8:
+        line.update({"value": main_res["cache_GBps"], "unit": "GB/s", "ms_per_step": main_res["us_per_step"] / 1e3,
+                     "us_per_token": main_res["us_per_token"],
+                     "config": {"workload": main_res["workload"], "batch": main_res and W.by_name(main_res["workload"]).batch,
+                                "context": W.by_name(main_res["workload"]).seqlen, "value_is": "cache bytes / whole gta_decode step"}})
+    else:
+        line.update({"value": main_res["tflops"], "unit": "TFLOP/s", "ms_per_step": main_res["ms_per_step"],
+                     "config": {"workload": main_res["workload"], "value_is": "algorithmic flops / whole gta_prefill call"}})
+    line["roofline"] = main_res["roofline"]
+    if "cpu_baseline" in main_res:
+        line["cpu_baseline"] = main_res.pop("cpu_baseline")
+    if pre is not None and main_res is not pre:
+        line["prefill"] = pre
+    if dec8 is not None and main_res is not dec8:
+        line["decode_b64_8k"] = dec8
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

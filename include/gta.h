@@ -138,6 +138,31 @@ GTA_API int gta_cache_append(const gta_config *cfg, const gta_cache *cache, cons
                      const void *k_new, const void *c_new, const int32_t *cu_new, int32_t batch,
                      int32_t max_new, void *hip_stream);
 
+/* ---- stage entry points: one stage of the pass on already projected inputs, in the launch
+ * configuration gta_prefill / gta_decode use (for stage-wise tests and per-kernel timing). ---- */
+
+/* Attention stage of the prefill (Sec. 3.3, reformulated form): for every map group g and token t,
+ * l_out[t, g*d_l : (g+1)*d_l] = sum_{j<=t} Softmax_j(q_g[t].k_{k(g)}[j] / sqrt(d_h)) c_{c(g)}[j].
+ *   q [total, n_q*d_h], k [total, n_k*d_h] (both already rotated), c [total, n_c*d_l],
+ *   l_out [total, n_q*d_l]; all device, element type = cfg->dtype; cu_seqlens as in gta_prefill. */
+GTA_API int gta_prefill_attention(const gta_config *cfg, const void *q, const void *k, const void *c,
+                                  const int32_t *cu_seqlens, int32_t batch, int64_t total_tokens,
+                                  int32_t max_seqlen, void *l_out, void *hip_stream);
+
+/* Split-K attention stage of the decode step (App. B.1.3) over the seq_lens[slot] rows ALREADY in
+ * the caches (nothing is appended): leaves one un-normalised partial (accumulator, running max,
+ * running sum) per (sequence, split, group) in `workspace`.
+ *   q  device fp32 [batch, n_q*d_h], already rotated; workspace sized by gta_workspace_bytes(DECODE) */
+GTA_API int gta_decode_attention(const gta_config *cfg, const float *q, const gta_cache *cache,
+                                 const int32_t *slots, int32_t batch, int32_t num_splits, void *workspace,
+                                 size_t workspace_bytes, void *hip_stream);
+
+/* Merges the partials gta_decode_attention left in `workspace` (same batch / num_splits) by their
+ * log-sum-exp weights:  l_out fp32 [batch, n_q*d_l] = the normalised group outputs L_g. */
+GTA_API int gta_decode_combine(const gta_config *cfg, const gta_cache *cache, const int32_t *slots,
+                               int32_t batch, int32_t num_splits, void *workspace, size_t workspace_bytes,
+                               float *l_out, void *hip_stream);
+
 /* Static string for a gta_status value. */
 GTA_API const char *gta_strerror(int code);
 

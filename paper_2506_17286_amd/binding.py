@@ -21,7 +21,7 @@ GTA_ERR_NULL, GTA_ERR_SHAPE, GTA_ERR_ALIGN, GTA_ERR_DTYPE = -1, -2, -3, -4
 GTA_ERR_UNSUPPORTED, GTA_ERR_WORKSPACE, GTA_ERR_HIP, GTA_ERR_CACHE_FULL = -5, -6, -7, -8
 
 EXPORTS = ["gta_workspace_bytes", "gta_prefill", "gta_decode", "gta_cache_append", "gta_strerror",
-           "gta_uses_tuned_kernels"]
+           "gta_uses_tuned_kernels", "gta_prefill_attention", "gta_decode_attention", "gta_decode_combine"]
 
 
 class gta_config(ctypes.Structure):
@@ -54,6 +54,9 @@ def load(path: Optional[str] = None) -> ctypes.CDLL:
     global _lib
     if _lib is not None and path is None:
         return _lib
+    # PyTorch ships its own HIP runtime: import it first so libgta.so binds to the SAME runtime
+    # (and thus the same device context and streams) instead of pulling in a second copy.
+    import torch  # noqa: F401
     p = path or LIB_PATH
     if not os.path.exists(p):
         raise FileNotFoundError(
@@ -69,6 +72,12 @@ def load(path: Optional[str] = None) -> ctypes.CDLL:
     lib.gta_decode.argtypes = [cfgp, wp, vp, i32, cp, vp, vp, i32, vp, sz, vp]
     lib.gta_cache_append.restype = ctypes.c_int
     lib.gta_cache_append.argtypes = [cfgp, cp, vp, vp, vp, vp, i32, i32, vp]
+    lib.gta_prefill_attention.restype = ctypes.c_int
+    lib.gta_prefill_attention.argtypes = [cfgp, vp, vp, vp, vp, i32, i64, i32, vp, vp]
+    lib.gta_decode_attention.restype = ctypes.c_int
+    lib.gta_decode_attention.argtypes = [cfgp, vp, cp, vp, i32, i32, vp, sz, vp]
+    lib.gta_decode_combine.restype = ctypes.c_int
+    lib.gta_decode_combine.argtypes = [cfgp, cp, vp, i32, i32, vp, sz, vp, vp]
     lib.gta_strerror.restype = ctypes.c_char_p
     lib.gta_strerror.argtypes = [ctypes.c_int]
     lib.gta_uses_tuned_kernels.restype = ctypes.c_int
@@ -166,6 +175,34 @@ def gta_cache_append(cfg: gta_config, cache: gta_cache, slots, k_new, c_new, cu_
                                  _stream(stream))
     if check:
         _check(rc, "gta_cache_append")
+    return rc
+
+
+def gta_prefill_attention(cfg: gta_config, q, k, c, cu_seqlens, batch: int, total_tokens: int, max_seqlen: int,
+                          l_out, stream=None, check: bool = True) -> int:
+    rc = load().gta_prefill_attention(ctypes.byref(cfg), _ptr(q), _ptr(k), _ptr(c), _ptr(cu_seqlens), batch,
+                                      total_tokens, max_seqlen, _ptr(l_out), _stream(stream))
+    if check:
+        _check(rc, "gta_prefill_attention")
+    return rc
+
+
+def gta_decode_attention(cfg: gta_config, q, cache: gta_cache, slots, batch: int, num_splits: int, workspace,
+                         stream=None, check: bool = True) -> int:
+    rc = load().gta_decode_attention(ctypes.byref(cfg), _ptr(q), ctypes.byref(cache), _ptr(slots), batch, num_splits,
+                                     _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream))
+    if check:
+        _check(rc, "gta_decode_attention")
+    return rc
+
+
+def gta_decode_combine(cfg: gta_config, cache: gta_cache, slots, batch: int, num_splits: int, workspace, l_out,
+                       stream=None, check: bool = True) -> int:
+    rc = load().gta_decode_combine(ctypes.byref(cfg), ctypes.byref(cache), _ptr(slots), batch, num_splits,
+                                   _ptr(workspace), workspace.numel() * workspace.element_size(), _ptr(l_out),
+                                   _stream(stream))
+    if check:
+        _check(rc, "gta_decode_combine")
     return rc
 
 

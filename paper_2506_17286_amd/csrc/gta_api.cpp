@@ -212,6 +212,71 @@ int gta_decode(const gta_config *cfg, const gta_weights *weights, const void *x_
   return generic_decode(d, *weights, x_new, batch, *cache, slots, out, ws, st);
 }
 
+int gta_prefill_attention(const gta_config *cfg, const void *q, const void *k, const void *c,
+                          const int32_t *cu_seqlens, int32_t batch, int64_t total_tokens, int32_t max_seqlen,
+                          void *l_out, void *hip_stream) {
+  Dims d;
+  int rc = make_dims(cfg, &d);
+  if (rc != GTA_OK) return rc;
+  if (!q || !k || !c || !l_out) return GTA_ERR_NULL;
+  if (batch <= 0 || batch > kMaxBatch || total_tokens < 0 || total_tokens > INT32_MAX || max_seqlen < 0)
+    return GTA_ERR_SHAPE;
+  if (!cu_seqlens && (total_tokens % batch != 0 || total_tokens / batch > max_seqlen)) return GTA_ERR_SHAPE;
+  if (misaligned(q) || misaligned(k) || misaligned(c) || misaligned(l_out) || ((uintptr_t)cu_seqlens & 3u))
+    return GTA_ERR_ALIGN;
+  if (total_tokens == 0 || max_seqlen == 0) return GTA_OK;
+  hipStream_t st = (hipStream_t)hip_stream;
+  if (tuned_prefill_supported(d) && attn_prefill_supported(d))
+    launch_attn_prefill_bf16(d, q, k, c, cu_seqlens, batch, total_tokens, max_seqlen, l_out, st);
+  else
+    launch_attn_prefill_rowwise(d, q, k, c, cu_seqlens, batch, total_tokens, max_seqlen, l_out, st);
+  return check_launch();
+}
+
+static int decode_stage_args(const gta_config *cfg, const gta_cache *cache, const int32_t *slots, int32_t batch,
+                             int32_t num_splits, void *workspace, size_t workspace_bytes, Dims *d, DecodeWs *ws) {
+  int rc = make_dims(cfg, d);
+  if (rc != GTA_OK) return rc;
+  if (!cache) return GTA_ERR_NULL;
+  if ((rc = check_cache(cache)) != GTA_OK) return rc;
+  if (batch <= 0 || batch > kMaxBatch || num_splits < 0 || (!slots && batch > cache->max_batch)) return GTA_ERR_SHAPE;
+  if ((uintptr_t)slots & 3u) return GTA_ERR_ALIGN;
+  if (!workspace || misaligned(workspace)) return GTA_ERR_WORKSPACE;
+  *ws = carve_decode(*d, true, batch, choose_splits(*d, batch, cache->max_seq, num_splits), workspace);
+  return ws->bytes > workspace_bytes ? GTA_ERR_WORKSPACE : GTA_OK;
+}
+
+int gta_decode_attention(const gta_config *cfg, const float *q, const gta_cache *cache, const int32_t *slots,
+                         int32_t batch, int32_t num_splits, void *workspace, size_t workspace_bytes,
+                         void *hip_stream) {
+  Dims d;
+  DecodeWs ws;
+  int rc = decode_stage_args(cfg, cache, slots, batch, num_splits, workspace, workspace_bytes, &d, &ws);
+  if (rc != GTA_OK) return rc;
+  if (!q) return GTA_ERR_NULL;
+  if (misaligned(q)) return GTA_ERR_ALIGN;
+  hipStream_t st = (hipStream_t)hip_stream;
+  launch_cached_len(*cache, slots, batch, ws.oldlen, st);
+  if (tuned_decode_supported(d)) tuned_decode_attention(d, q, ws.oldlen, *cache, slots, batch, ws.splits, ws.part, st);
+  else generic_decode_attention(d, q, ws.oldlen, *cache, slots, batch, ws.splits, ws.part, st);
+  return check_launch();
+}
+
+int gta_decode_combine(const gta_config *cfg, const gta_cache *cache, const int32_t *slots, int32_t batch,
+                       int32_t num_splits, void *workspace, size_t workspace_bytes, float *l_out,
+                       void *hip_stream) {
+  Dims d;
+  DecodeWs ws;
+  int rc = decode_stage_args(cfg, cache, slots, batch, num_splits, workspace, workspace_bytes, &d, &ws);
+  if (rc != GTA_OK) return rc;
+  if (!l_out) return GTA_ERR_NULL;
+  if (misaligned(l_out)) return GTA_ERR_ALIGN;
+  hipStream_t st = (hipStream_t)hip_stream;
+  if (tuned_decode_supported(d)) tuned_decode_combine(d, ws.part, ws.oldlen, ws.splits, batch, l_out, st);
+  else generic_decode_combine(d, ws.part, ws.oldlen, ws.splits, batch, l_out, st);
+  return check_launch();
+}
+
 int gta_cache_append(const gta_config *cfg, const gta_cache *cache, const int32_t *slots, const void *k_new,
                      const void *c_new, const int32_t *cu_new, int32_t batch, int32_t max_new, void *hip_stream) {
   Dims d;

@@ -354,11 +354,11 @@ __global__ __launch_bounds__(512) void decode_decoder_kernel(Dims d, const float
 }
 
 template <class S>
-void launch_attn(const Dims &d, const gta_cache &cache, const int32_t *slots, int batch, const DecodeWs &ws,
-                 float *pacc, float *pml, hipStream_t st) {
-  dim3 grid(ws.splits, batch);
-  decode_attn_kernel<S><<<grid, 256, 0, st>>>(ws.q, ws.oldlen, (const bf16 *)cache.k, (const bf16 *)cache.c, slots,
-                                             cache.max_seq, ws.splits, d.scale * 1.4426950408889634f, pacc, pml);
+void launch_attn(const Dims &d, const float *q, const int32_t *oldlen, const gta_cache &cache, const int32_t *slots,
+                 int batch, int splits, float *pacc, float *pml, hipStream_t st) {
+  dim3 grid(splits, batch);
+  decode_attn_kernel<S><<<grid, 256, 0, st>>>(q, oldlen, (const bf16 *)cache.k, (const bf16 *)cache.c, slots,
+                                             cache.max_seq, splits, d.scale * 1.4426950408889634f, pacc, pml);
 }
 
 typedef DecShape<128, 4, 1, 1, 1, 8, 2> Shape1B;      // 4 maps, 4 keys of 128, one latent of 512
@@ -376,16 +376,27 @@ bool tuned_decode_supported(const Dims &d) {
   return matches<Shape1B>(d) || matches<ShapeWide>(d);
 }
 
+void tuned_decode_attention(const Dims &d, const float *q, const int32_t *oldlen, const gta_cache &cache,
+                            const int32_t *slots, int batch, int splits, float *part, hipStream_t st) {
+  float *pacc = part;
+  float *pml = part + (int64_t)batch * splits * d.nq * d.dl;
+  if (matches<Shape1B>(d)) launch_attn<Shape1B>(d, q, oldlen, cache, slots, batch, splits, pacc, pml, st);
+  else launch_attn<ShapeWide>(d, q, oldlen, cache, slots, batch, splits, pacc, pml, st);
+}
+
+void tuned_decode_combine(const Dims &d, const float *part, const int32_t *oldlen, int splits, int batch, float *L,
+                          hipStream_t st) {
+  const float *pml = part + (int64_t)batch * splits * d.nq * d.dl;
+  decode_combine_kernel<<<dim3((d.dl + 255) / 256, d.nq, batch), 256, splits * sizeof(float), st>>>(
+      d, part, pml, oldlen, splits, L);
+}
+
 int tuned_decode(const Dims &d, const gta_weights &w, const void *x_new, int batch, const gta_cache &cache,
                  const int32_t *slots, void *out, const DecodeWs &ws, hipStream_t st) {
   // Sec. 3.2 projections of the new tokens, RoPE at position seq_len, append to the caches
   generic_decode_project(d, w, x_new, batch, cache, slots, ws, st);
-  float *pacc = ws.part;
-  float *pml = ws.part + (int64_t)batch * ws.splits * d.nq * d.dl;
-  if (matches<Shape1B>(d)) launch_attn<Shape1B>(d, cache, slots, batch, ws, pacc, pml, st);
-  else launch_attn<ShapeWide>(d, cache, slots, batch, ws, pacc, pml, st);
-  decode_combine_kernel<<<dim3((d.dl + 255) / 256, d.nq, batch), 256, ws.splits * sizeof(float), st>>>(
-      d, pacc, pml, ws.oldlen, ws.splits, ws.l);
+  tuned_decode_attention(d, ws.q, ws.oldlen, cache, slots, batch, ws.splits, ws.part, st);
+  tuned_decode_combine(d, ws.part, ws.oldlen, ws.splits, batch, ws.l, st);
   dim3 grid(d.nh, (batch + kRows - 1) / kRows);
   const size_t smem = (size_t)kRows * (d.dl + 512) * sizeof(float);
   if (w.wo) {

@@ -227,6 +227,15 @@ __global__ void finalize_decode_kernel(Dims d, const float *praw, int batch, flo
   }
 }
 
+// Stage entry support: attend over the rows already cached (no append): "old length" = seq_len - 1.
+__global__ void cached_len_kernel(CacheView cv, int batch, int32_t *oldlen) {
+  int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= batch) return;
+  int slot = cv.slots ? cv.slots[b] : b;
+  int n = (slot >= 0 && slot < cv.max_batch) ? cv.seq_lens[slot] : 0;
+  oldlen[b] = (n > cv.max_seq ? cv.max_seq : n) - 1;
+}
+
 __global__ void decode_commit_kernel(CacheView cv, const int32_t *oldlen, int batch) {
   int b = blockIdx.x * blockDim.x + threadIdx.x;
   if (b >= batch) return;
@@ -540,11 +549,34 @@ void generic_decode_project(const Dims &d, const gta_weights &w, const void *x_n
   else decode_project_impl<float>(d, w, (const float *)x_new, batch, cache, slots, ws, st);
 }
 
-void launch_attn_prefill_rowwise_bf16(const Dims &d, const void *q, const void *k, const void *c, const int32_t *cu,
-                                      int batch, int64_t total, int max_len, void *L, hipStream_t st) {
+void launch_cached_len(const gta_cache &cache, const int32_t *slots, int batch, int32_t *oldlen, hipStream_t st) {
+  cached_len_kernel<<<grid1d(batch), 256, 0, st>>>(view_of(&cache, slots), batch, oldlen);
+}
+
+void generic_decode_attention(const Dims &d, const float *q, const int32_t *oldlen, const gta_cache &cache,
+                              const int32_t *slots, int batch, int splits, float *part, hipStream_t st) {
+  CacheView cv = view_of(&cache, slots);
+  dim3 agrid(splits, d.nq, batch);
+  if (d.dtype == GTA_BF16)
+    attn_decode_generic_kernel<bf16><<<agrid, 64, d.dh * sizeof(float), st>>>(d, q, oldlen, cv, splits, part);
+  else
+    attn_decode_generic_kernel<float><<<agrid, 64, d.dh * sizeof(float), st>>>(d, q, oldlen, cv, splits, part);
+}
+
+void generic_decode_combine(const Dims &d, const float *part, const int32_t *oldlen, int splits, int batch, float *L,
+                            hipStream_t st) {
+  decode_combine_kernel<<<dim3(d.nq, batch), 256, 0, st>>>(d, part, oldlen, splits, L);
+}
+
+void launch_attn_prefill_rowwise(const Dims &d, const void *q, const void *k, const void *c, const int32_t *cu,
+                                 int batch, int64_t total, int max_len, void *L, hipStream_t st) {
   dim3 agrid((max_len + 3) / 4, d.nq, batch);
-  attn_prefill_generic_kernel<bf16, bf16><<<agrid, 256, 4 * d.dh * sizeof(float), st>>>(
-      d, (const bf16 *)q, (const bf16 *)k, (const bf16 *)c, cu, (int)(total / batch), max_len, (bf16 *)L);
+  if (d.dtype == GTA_BF16)
+    attn_prefill_generic_kernel<bf16, bf16><<<agrid, 256, 4 * d.dh * sizeof(float), st>>>(
+        d, (const bf16 *)q, (const bf16 *)k, (const bf16 *)c, cu, (int)(total / batch), max_len, (bf16 *)L);
+  else
+    attn_prefill_generic_kernel<float, float><<<agrid, 256, 4 * d.dh * sizeof(float), st>>>(
+        d, (const float *)q, (const float *)k, (const float *)c, cu, (int)(total / batch), max_len, (float *)L);
 }
 
 void launch_decode_commit(const gta_cache &cache, const int32_t *slots, const int32_t *oldlen, int batch,

@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stddef.h>
 #include <stdint.h>
+#include <stdio.h>
+#include <stdlib.h>
 
 #include "gta.h"
 
@@ -73,14 +75,26 @@ void launch_decode_commit(const gta_cache &cache, const int32_t *slots, const in
                           hipStream_t st);
 void generic_out_proj_f32in(const Dims &d, const gta_weights &w, const float *O, int M, void *out, hipStream_t st);
 
-void launch_attn_prefill_rowwise_bf16(const Dims &d, const void *q, const void *k, const void *c, const int32_t *cu,
-                                      int batch, int64_t total, int max_len, void *L, hipStream_t st);
+void launch_attn_prefill_rowwise(const Dims &d, const void *q, const void *k, const void *c, const int32_t *cu,
+                                 int batch, int64_t total, int max_len, void *L, hipStream_t st);
+void launch_cached_len(const gta_cache &cache, const int32_t *slots, int batch, int32_t *oldlen, hipStream_t st);
+void generic_decode_attention(const Dims &d, const float *q, const int32_t *oldlen, const gta_cache &cache,
+                              const int32_t *slots, int batch, int splits, float *part, hipStream_t st);
+void generic_decode_combine(const Dims &d, const float *part, const int32_t *oldlen, int splits, int batch, float *L,
+                            hipStream_t st);
 void launch_rowmap(const int32_t *cu, int batch, int64_t total, int32_t *seq_id, int32_t *pos,
                    hipStream_t st);
 void launch_rope_table(float2 *tab, int max_pos, int dh, double base, hipStream_t st);
 void launch_prefill_commit(const gta_cache &cache, const int32_t *slots, const int32_t *cu,
                            int batch, int64_t total, hipStream_t st);
 
-static inline int check_launch() { return hipGetLastError() == hipSuccess ? GTA_OK : GTA_ERR_HIP; }
+// hipGetLastError after the launches of a call; with GTA_DEBUG set in the environment the HIP error
+// string goes to stderr (the only thing the library ever prints).
+static inline int check_launch() {
+  hipError_t e = hipGetLastError();
+  if (e == hipSuccess) return GTA_OK;
+  if (getenv("GTA_DEBUG")) fprintf(stderr, "libgta: HIP error %d: %s\n", (int)e, hipGetErrorString(e));
+  return GTA_ERR_HIP;
+}
 
 }  // namespace gta

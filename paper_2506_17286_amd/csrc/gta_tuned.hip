@@ -16,7 +16,7 @@ int tuned_prefill(const Dims &d, const gta_weights &w, const void *x, const int3
   if (cache) launch_prefill_commit(*cache, slots, cu, batch, total, st);
   // Sec. 3.3: one causal softmax map per group applied to the latent values
   if (attn_prefill_supported(d)) launch_attn_prefill_bf16(d, ws.q, ws.k, ws.c, cu, batch, total, max_len, ws.l, st);
-  else launch_attn_prefill_rowwise_bf16(d, ws.q, ws.k, ws.c, cu, batch, total, max_len, ws.l, st);
+  else launch_attn_prefill_rowwise(d, ws.q, ws.k, ws.c, cu, batch, total, max_len, ws.l, st);
   // Sec. 3.2 value decoder with the gate in the epilogue, then the optional W_O
   if (w.wo) {
     launch_decoder_gemm(d, ws.l, w.wp, ws.g, ws.o, M, st);
