@@ -89,7 +89,7 @@ DecodeWs carve_decode(const Dims &d, bool with_wo, int batch, int splits, void *
   DecodeWs w{};
   const size_t b = (size_t)batch;
   w.splits = splits;
-  w.praw = cv.take<float>(b * d.wtot * 4);
+  w.praw = cv.take<float>(b * d.wtot * 4 * 16);   // up to 16 split-K partials
   w.q = cv.take<float>(b * d.wq_w * 4);
   w.g = cv.take<float>(b * d.wg_w * 4);
   w.part = cv.take<float>(b * splits * d.nq * (size_t)(d.dl + 2) * 4);

@@ -17,6 +17,7 @@ namespace {
 
 typedef __bf16 bf16;
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 
 template <int CTRL>
 __device__ __forceinline__ float dpp_mov(float v) {
@@ -307,49 +308,220 @@ __global__ __launch_bounds__(256) void decode_combine_kernel(Dims d, const float
   Lr[c] = a0 + a1;
 }
 
-// Value decoder and gate (Sec. 3.2) for one head and up to 8 sequences:
-// O_i = (L_g W_{P,i}) * Sigmoid(gate pre-activation of the new token).
-// 512 threads = d_h columns x (512 / d_h) slices of the latent dimension, reduced through LDS.
-constexpr int kRows = 8;
-
-template <typename TO>
-__global__ __launch_bounds__(512) void decode_decoder_kernel(Dims d, const float *__restrict__ L, int batch,
-                                                             const float *__restrict__ G,
-                                                             const bf16 *__restrict__ wp, TO *__restrict__ out) {
+// Tail of the decode step in ONE launch, for one head and ROWS sequences per workgroup:
+//   1. log-sum-exp weights of the context splits and the combined, normalised group output L_g,
+//   2. value decoder and gate (Sec. 3.2): O_i = (L_g W_{P,i}) * Sigmoid(gate pre-activation of the
+//      new token); 512 threads = d_h columns x (512 / d_h) slices of the latent dimension,
+//   3. bookkeeping: seq_lens[slot] += 1, or the CACHE_FULL flag (head 0's workgroup only).
+template <typename TO, int ROWS>
+__global__ __launch_bounds__(512) void decode_tail_kernel(Dims d, const float *__restrict__ pacc,
+                                                          const float *__restrict__ pml,
+                                                          const int32_t *__restrict__ oldlen, int splits, int batch,
+                                                          const float *__restrict__ G, const bf16 *__restrict__ wp,
+                                                          TO *__restrict__ out, int32_t *seq_lens, int32_t *status,
+                                                          const int32_t *__restrict__ slots, int max_batch) {
   extern __shared__ float smem[];
-  float *Ls = smem;                       // [kRows][dl]
-  float *red = smem + kRows * d.dl;       // [nsl][kRows][dh]
-  const int tid = threadIdx.x;
-  const int head = blockIdx.x, g = head / d.hpq, b0 = blockIdx.y * kRows;
-  for (int i = tid; i < kRows * d.dl; i += 512) {
-    const int r = i / d.dl, c = i % d.dl, b = b0 + r;
-    Ls[i] = b < batch ? L[((int64_t)b * d.nq + g) * d.dl + c] : 0.f;
+  float *Ls = smem;                          // [ROWS][dl]
+  float *red = Ls + ROWS * d.dl;             // [8 waves][ROWS][dh] and, earlier, [4][128] float4
+  float *wt = red + max(8 * ROWS * d.dh, 2048);   // [ROWS][splits]
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int head = blockIdx.x, g = head / d.hpq, b0 = blockIdx.y * ROWS;
+  if (head == 0 && tid < ROWS && b0 + tid < batch) {
+    const int b = b0 + tid, slot = slots ? slots[b] : b;
+    if (slot >= 0 && slot < max_batch) {
+      if (oldlen[b] >= 0) seq_lens[slot] = oldlen[b] + 1;
+      else status[slot] = GTA_ERR_CACHE_FULL;
+    }
+  }
+  for (int r = wave; r < ROWS; r += 8) {
+    const int b = b0 + r;
+    const bool live = b < batch && oldlen[b] >= 0;
+    const float *pm = pml + ((int64_t)b * splits * d.nq + g) * 2;
+    const int64_t ms = (int64_t)d.nq * 2;
+    float mx = -INFINITY;
+    if (live)
+      for (int s = lane; s < splits; s += 64) mx = fmaxf(mx, pm[s * ms]);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
+    float ls = 0.f;
+    if (live)
+      for (int s = lane; s < splits; s += 64) {
+        const float m = pm[s * ms];
+        if (m > -INFINITY) ls += exp2f(m - mx) * pm[s * ms + 1];
+      }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) ls += __shfl_xor(ls, o, 64);
+    const float inv = 1.0f / ls;
+    for (int s = lane; s < splits; s += 64) {
+      float w = 0.f;
+      if (live) {
+        const float m = pm[s * ms];
+        if (m > -INFINITY) w = exp2f(m - mx) * inv;
+      }
+      wt[r * splits + s] = w;
+    }
   }
   __syncthreads();
-  const int e = tid % d.dh, sl = tid / d.dh, nsl = 512 / d.dh;
-  const int per = (d.dl + nsl - 1) / nsl;
-  const int a0 = sl * per, a1 = min(d.dl, a0 + per);
-  float z[kRows];
+  // combined group output: thread = (4 columns, one of 4 split phases); 8 independent 16-byte loads
+  // in flight per thread, the 4 phases are summed through LDS
+  const int64_t as4 = (int64_t)d.nq * d.dl / 4;
+  const int nc4 = d.dl / 4;
+  float4 *red4 = reinterpret_cast<float4 *>(red);          // [4 phases][nc4], reused below
+  for (int r = 0; r < ROWS; ++r) {
+    const int b = b0 + r;
+    const bool live = b < batch && oldlen[b] >= 0;
+    for (int c0 = 0; c0 < nc4; c0 += 128) {
+      const int c4 = c0 + (tid & 127), ph = tid >> 7;
+      float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (live && c4 < nc4) {
+        const float4 *pa = reinterpret_cast<const float4 *>(pacc + ((int64_t)b * splits * d.nq + g) * d.dl) + c4;
+        const float *w = wt + r * splits;
+        for (int s0 = ph; s0 < splits; s0 += 32) {
+          float4 v[8];
+          float ww[8];
 #pragma unroll
-  for (int r = 0; r < kRows; ++r) z[r] = 0.f;
-  const bf16 *wcol = wp + (int64_t)head * d.dl * d.dh + e;
-#pragma unroll 4
-  for (int a = a0; a < a1; ++a) {
-    const float wv = (float)wcol[(int64_t)a * d.dh];
+          for (int u = 0; u < 8; ++u) {
+            const int s = s0 + 4 * u;
+            ww[u] = s < splits ? w[s] : 0.f;
+            v[u] = ww[u] != 0.f ? pa[s * as4] : make_float4(0.f, 0.f, 0.f, 0.f);
+          }
 #pragma unroll
-    for (int r = 0; r < kRows; ++r) z[r] = fmaf(Ls[r * d.dl + a], wv, z[r]);
+          for (int u = 0; u < 8; ++u) {
+            a.x = fmaf(ww[u], v[u].x, a.x); a.y = fmaf(ww[u], v[u].y, a.y);
+            a.z = fmaf(ww[u], v[u].z, a.z); a.w = fmaf(ww[u], v[u].w, a.w);
+          }
+        }
+      }
+      red4[ph * 128 + (tid & 127)] = a;
+      __syncthreads();
+      if (tid < 128 && c4 < nc4) {
+        const float4 x0 = red4[tid], x1 = red4[128 + tid], x2 = red4[256 + tid], x3 = red4[384 + tid];
+        float4 o;
+        o.x = (x0.x + x1.x) + (x2.x + x3.x); o.y = (x0.y + x1.y) + (x2.y + x3.y);
+        o.z = (x0.z + x1.z) + (x2.z + x3.z); o.w = (x0.w + x1.w) + (x2.w + x3.w);
+        reinterpret_cast<float4 *>(Ls + r * d.dl)[c4] = o;
+      }
+      __syncthreads();
+    }
   }
+  // decoder: thread = (8 output columns, one of 512*8/d_h latent phases); all its weight loads
+  // (16 bytes each) are independent; phases are summed by shuffles and through LDS
+  const int ncg = d.dh / 8, cg = tid % ncg, aph = tid / ncg, naph = 512 / ncg;
+  float z[ROWS][8];
 #pragma unroll
-  for (int r = 0; r < kRows; ++r) red[(sl * kRows + r) * d.dh + e] = z[r];
+  for (int r = 0; r < ROWS; ++r)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) z[r][e] = 0.f;
+  const bf16 *wbase = wp + (int64_t)head * d.dl * d.dh + cg * 8;
+#pragma unroll 16
+  for (int a = aph; a < d.dl; a += naph) {
+    const bf16x8 w8 = *reinterpret_cast<const bf16x8 *>(wbase + (int64_t)a * d.dh);
+#pragma unroll
+    for (int r = 0; r < ROWS; ++r) {
+      const float lv = Ls[r * d.dl + a];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) z[r][e] = fmaf(lv, (float)w8[e], z[r][e]);
+    }
+  }
+  // lanes with equal cg inside a wave are ncg apart
+#pragma unroll
+  for (int r = 0; r < ROWS; ++r)
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+      for (int o = ncg; o < 64; o <<= 1) z[r][e] += __shfl_xor(z[r][e], o, 64);
+  if (lane < ncg) {
+#pragma unroll
+    for (int r = 0; r < ROWS; ++r)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) red[(wave * ROWS + r) * d.dh + cg * 8 + e] = z[r][e];
+  }
   __syncthreads();
-  for (int i = tid; i < kRows * d.dh; i += 512) {
+  for (int i = tid; i < ROWS * d.dh; i += 512) {
     const int r = i / d.dh, ee = i % d.dh, b = b0 + r;
     if (b >= batch) continue;
     float v = 0.f;
-    for (int q = 0; q < nsl; ++q) v += red[(q * kRows + r) * d.dh + ee];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) v += red[(q * ROWS + r) * d.dh + ee];
     const int col = head * d.dh + ee;
     if (d.gate) v *= 1.0f / (1.0f + __expf(-G[(int64_t)b * d.wg_w + col]));
     out[(int64_t)b * d.wg_w + col] = (TO)v;
+  }
+}
+
+template <typename TO, int ROWS>
+void launch_tail(const Dims &d, const float *pacc, const float *pml, const DecodeWs &ws, int batch, const bf16 *wp,
+                 TO *out, const gta_cache &cache, const int32_t *slots, hipStream_t st) {
+  dim3 grid(d.nh, (batch + ROWS - 1) / ROWS);
+  const size_t red = (size_t)(8 * ROWS * d.dh > 2048 ? 8 * ROWS * d.dh : 2048);
+  const size_t smem = ((size_t)ROWS * d.dl + red + (size_t)ROWS * ws.splits) * sizeof(float);
+  decode_tail_kernel<TO, ROWS><<<grid, 512, smem, st>>>(d, pacc, pml, ws.oldlen, ws.splits, batch, ws.g, wp, out,
+                                                        cache.seq_lens, cache.status, slots, cache.max_batch);
+}
+
+template <typename TO>
+void launch_tail_any(const Dims &d, const float *pacc, const float *pml, const DecodeWs &ws, int batch,
+                     const bf16 *wp, TO *out, const gta_cache &cache, const int32_t *slots, hipStream_t st) {
+  // about 128 workgroups: one row per workgroup for small batches, up to 8 for large ones
+  const int rows = batch * d.nh / 128;
+  if (rows >= 8) launch_tail<TO, 8>(d, pacc, pml, ws, batch, wp, out, cache, slots, st);
+  else if (rows >= 4) launch_tail<TO, 4>(d, pacc, pml, ws, batch, wp, out, cache, slots, st);
+  else if (rows >= 2) launch_tail<TO, 2>(d, pacc, pml, ws, batch, wp, out, cache, slots, st);
+  else launch_tail<TO, 1>(d, pacc, pml, ws, batch, wp, out, cache, slots, st);
+}
+
+// Sums the split-K partials of the new tokens' projections, rotates q and k at position
+// seq_lens[slot] (App. B.1.1; angle reduced mod 2 pi in fp64, then fp32 sincos), appends the key and
+// latent rows to the caches (App. B.1.3) and leaves q and the gate pre-activation in fp32.
+struct RopeFreq { double f[64]; };   // base^(-2j/d_h), j < d_h/2 <= 64, computed on the host
+
+__global__ __launch_bounds__(256) void decode_finalize_kernel(Dims d, RopeFreq rf, const float *__restrict__ part,
+                                                              int nsum, int batch, float *__restrict__ Qo,
+                                                              float *__restrict__ Go, int32_t *__restrict__ oldlen,
+                                                              bf16 *__restrict__ kc, bf16 *__restrict__ cc,
+                                                              const int32_t *__restrict__ seq_lens,
+                                                              const int32_t *__restrict__ slots, int max_batch,
+                                                              int max_seq) {
+  const int64_t idx = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+  if (idx >= (int64_t)batch * d.wtot) return;
+  const int b = (int)(idx / d.wtot), col = (int)(idx % d.wtot);
+  const int slot = slots ? slots[b] : b;
+  const bool slot_ok = slot >= 0 && slot < max_batch;
+  const int p = slot_ok ? seq_lens[slot] : 0;
+  const bool ok = slot_ok && p >= 0 && p < max_seq;
+  if (col == 0) oldlen[b] = ok ? p : -1;
+  if (!ok) return;
+  const int64_t pstride = (int64_t)batch * d.wtot;
+  const int qk_w = d.wq_w + d.wk_w;
+  const int half = d.dh / 2, e = col % d.dh;
+  const bool rot = d.rope && col < qk_w;
+  const int64_t pidx = rot ? (e < half ? idx + half : idx - half) : idx;
+  // all partial loads are independent: issue them together (nsum <= 16)
+  float pv[16], pu[16];
+#pragma unroll
+  for (int s = 0; s < 16; ++s) {
+    pv[s] = s < nsum ? part[s * pstride + idx] : 0.f;
+    pu[s] = (rot && s < nsum) ? part[s * pstride + pidx] : 0.f;
+  }
+  float v = 0.f, u = 0.f;
+#pragma unroll
+  for (int s = 0; s < 16; ++s) { v += pv[s]; u += pu[s]; }
+  if (rot) {
+    const double ang = (double)p * rf.f[e % half];
+    const double k = rint(ang * 0.15915494309189535);
+    double r = fma(-k, 6.283185307179586, ang);
+    r = fma(-k, 2.4492935982947064e-16, r);
+    float sn, cs;
+    sincosf((float)r, &sn, &cs);
+    v = e < half ? v * cs - u * sn : v * cs + u * sn;
+  }
+  if (col < d.wq_w) {
+    Qo[(int64_t)b * d.wq_w + col] = v;
+  } else if (col < qk_w) {
+    kc[((int64_t)slot * max_seq + p) * d.wk_w + (col - d.wq_w)] = (bf16)v;
+  } else if (col < qk_w + d.wc_w) {
+    cc[((int64_t)slot * max_seq + p) * d.wc_w + (col - qk_w)] = (bf16)v;
+  } else {
+    Go[(int64_t)b * d.wg_w + (col - qk_w - d.wc_w)] = v;
   }
 }
 
@@ -394,18 +566,27 @@ void tuned_decode_combine(const Dims &d, const float *part, const int32_t *oldle
 int tuned_decode(const Dims &d, const gta_weights &w, const void *x_new, int batch, const gta_cache &cache,
                  const int32_t *slots, void *out, const DecodeWs &ws, hipStream_t st) {
   // Sec. 3.2 projections of the new tokens, RoPE at position seq_len, append to the caches
-  generic_decode_project(d, w, x_new, batch, cache, slots, ws, st);
+  if (gemm_shapes_supported(d)) {
+    const int ks = skinny_ksplit(d, batch);
+    launch_skinny_proj(d, w, x_new, batch, ws.praw, ks, st);
+    RopeFreq rf;
+    for (int j = 0; j < d.dh / 2; ++j) rf.f[j] = pow(d.rope_base, -2.0 * (double)j / (double)d.dh);
+    const int64_t n = (int64_t)batch * d.wtot;
+    decode_finalize_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(
+        d, rf, ws.praw, ks, batch, ws.q, ws.g, ws.oldlen, (bf16 *)cache.k, (bf16 *)cache.c, cache.seq_lens, slots,
+        cache.max_batch, cache.max_seq);
+  } else {
+    generic_decode_project(d, w, x_new, batch, cache, slots, ws, st);
+  }
   tuned_decode_attention(d, ws.q, ws.oldlen, cache, slots, batch, ws.splits, ws.part, st);
-  tuned_decode_combine(d, ws.part, ws.oldlen, ws.splits, batch, ws.l, st);
-  dim3 grid(d.nh, (batch + kRows - 1) / kRows);
-  const size_t smem = (size_t)kRows * (d.dl + 512) * sizeof(float);
+  const float *pacc = ws.part;
+  const float *pml = ws.part + (int64_t)batch * ws.splits * d.nq * d.dl;
   if (w.wo) {
-    decode_decoder_kernel<float><<<grid, 512, smem, st>>>(d, ws.l, batch, ws.g, (const bf16 *)w.wp, ws.o);
+    launch_tail_any<float>(d, pacc, pml, ws, batch, (const bf16 *)w.wp, ws.o, cache, slots, st);
     generic_out_proj_f32in(d, w, ws.o, batch, out, st);
   } else {
-    decode_decoder_kernel<bf16><<<grid, 512, smem, st>>>(d, ws.l, batch, ws.g, (const bf16 *)w.wp, (bf16 *)out);
+    launch_tail_any<bf16>(d, pacc, pml, ws, batch, (const bf16 *)w.wp, (bf16 *)out, cache, slots, st);
   }
-  launch_decode_commit(cache, slots, ws.oldlen, batch, st);
   return check_launch();
 }
 

@@ -295,6 +295,50 @@ __global__ __launch_bounds__(T::NT) void plain_gemm_kernel(PlainArgs a) {
   }
 }
 
+// ------------------------------------------------------------------------------ decode projection
+// Few rows (one new token per sequence) against all four weight matrices: weight-streaming bound.
+// Split-K over H so that several hundred workgroups pull on HBM at once; every (k-split, n-tile)
+// writes an fp32 partial that the finalize kernel sums before RoPE / cache append.
+struct SkinnyArgs {
+  const bf16 *x; int64_t lda; int M, K;
+  const bf16 *w[4]; int width[4];
+  float *part;            // [ksplit, M, wtot]
+  int ksplit, wtot;
+};
+
+template <class T>
+__global__ __launch_bounds__(T::NT) void skinny_proj_kernel(SkinnyArgs a) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  const int ntn = a.wtot / T::BN, ntm = (a.M + T::BM - 1) / T::BM;
+  const int ks = blockIdx.x / (ntn * ntm), rem = blockIdx.x % (ntn * ntm);
+  const int mt = rem / ntn, nt = rem % ntn;
+  int n_seg = nt * T::BN, seg = 0;
+  while (n_seg >= a.width[seg]) { n_seg -= a.width[seg]; ++seg; }
+  const int m0 = mt * T::BM, klen = a.K / a.ksplit, k0 = ks * klen;
+  f32x16 acc[T::TN][T::TM];
+  zero_acc<T>(acc);
+  gemm_mainloop<T>(a.x + k0, a.lda, a.M, m0, a.w[seg] + (int64_t)k0 * a.width[seg], a.width[seg], n_seg, klen, smem, acc);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wn = wave % T::WGN, wm = wave / T::WGN;
+  float *prow = a.part + (int64_t)ks * a.M * a.wtot;
+#pragma unroll
+  for (int tm = 0; tm < T::TM; ++tm) {
+    const int m = m0 + wm * T::WM + tm * 32 + (lane & 31);
+    if (m >= a.M) continue;
+#pragma unroll
+    for (int tn = 0; tn < T::TN; ++tn)
+#pragma unroll
+      for (int rq = 0; rq < 4; ++rq) {
+        const int n = nt * T::BN + wn * T::WN + tn * 32 + rq * 8 + (lane >> 5) * 4;
+        *reinterpret_cast<float4 *>(prow + (int64_t)m * a.wtot + n) =
+            make_float4(acc[tn][tm][rq * 4], acc[tn][tm][rq * 4 + 1], acc[tn][tm][rq * 4 + 2], acc[tn][tm][rq * 4 + 3]);
+      }
+  }
+}
+
+typedef GemmTile<32, 128, 64, 1, 4> TileSkinny32;
+typedef GemmTile<64, 128, 64, 1, 4> TileSkinny64;
+
 typedef GemmTile<256, 256, 64, 2, 2> TileBig;    // wave tile 128 x 128
 typedef GemmTile<256, 128, 64, 4, 1> TileHead;   // one 128-wide head per workgroup, wave tile 64(m) x 128(n)
 
@@ -341,6 +385,33 @@ void launch_proj_gemm(const Dims &d, const gta_weights &w, const void *x, int M,
   } else {
     const int nt = (d.wtot / 128) * ((M + 255) / 256);
     launch<TileHead>(proj_gemm_kernel<TileHead>, a, nt, st);
+  }
+}
+
+int skinny_ksplit(const Dims &d, int M) {
+  const int ktiles = d.H / 64;
+  const int tiles = (d.wtot / 128) * ((M + 63) / 64);
+  int want = (768 + tiles - 1) / tiles;
+  if (want > 16) want = 16;
+  int ks = 1;
+  for (int c = 1; c <= want; ++c)
+    if (ktiles % c == 0) ks = c;
+  return ks;
+}
+
+// [M, wtot] = X . [W_Q | W_K | W_C | W_G] as `ksplit` fp32 partials (M small)
+void launch_skinny_proj(const Dims &d, const gta_weights &w, const void *x, int M, float *part, int ksplit,
+                        hipStream_t st) {
+  SkinnyArgs a{};
+  a.x = (const bf16 *)x; a.lda = d.H; a.M = M; a.K = d.H;
+  const void *wm[4] = {w.wq, w.wk, w.wc, w.wg};
+  const int wd[4] = {d.wq_w, d.wk_w, d.wc_w, d.wg_w};
+  for (int i = 0; i < 4; ++i) { a.w[i] = (const bf16 *)wm[i]; a.width[i] = wd[i]; }
+  a.part = part; a.ksplit = ksplit; a.wtot = d.wtot;
+  if (M <= 32) {
+    launch<TileSkinny32>(skinny_proj_kernel<TileSkinny32>, a, ksplit * (d.wtot / 128) * ((M + 31) / 32), st);
+  } else {
+    launch<TileSkinny64>(skinny_proj_kernel<TileSkinny64>, a, ksplit * (d.wtot / 128) * ((M + 63) / 64), st);
   }
 }
 

@@ -194,7 +194,7 @@ __global__ void prefill_commit_kernel(CacheView cv, const int32_t *cu, int batch
 
 // Decode: position = tokens already cached; the new key / latent row is appended at that row.
 template <typename T>
-__global__ void finalize_decode_kernel(Dims d, const float *praw, int batch, float *Qo, float *Go,
+__global__ void finalize_decode_kernel(Dims d, const float *praw, int nsum, int batch, float *Qo, float *Go,
                                        int32_t *oldlen, CacheView cv) {
   int64_t idx = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
   if (idx >= (int64_t)batch * d.wtot) return;
@@ -206,15 +206,22 @@ __global__ void finalize_decode_kernel(Dims d, const float *praw, int batch, flo
   bool ok = slot_ok && p >= 0 && p < cv.max_seq;
   if (col == 0) oldlen[b] = ok ? p : -1;
   if (!ok) return;
-  float v = praw[idx];
+  // the projection may arrive as `nsum` split-K partials of [batch, wtot]
+  const int64_t pstride = (int64_t)batch * d.wtot;
+  auto raw = [&](int64_t i) {
+    float a = praw[i];
+    for (int s = 1; s < nsum; ++s) a += praw[s * pstride + i];
+    return a;
+  };
+  float v = raw(idx);
   const int qk_w = d.wq_w + d.wk_w;
   if (col < qk_w && d.rope) {
     int e = col % d.dh, half = d.dh / 2;
     double ang = (double)p * pow(d.rope_base, -2.0 * (double)(e % half) / (double)d.dh);
     double sn, cs;
     sincos(ang, &sn, &cs);
-    if (e < half) v = v * (float)cs - praw[idx + half] * (float)sn;
-    else          v = v * (float)cs + praw[idx - half] * (float)sn;
+    if (e < half) v = v * (float)cs - raw(idx + half) * (float)sn;
+    else          v = v * (float)cs + raw(idx - half) * (float)sn;
   }
   if (col < d.wq_w) {
     Qo[(int64_t)b * d.wq_w + col] = v;
@@ -482,7 +489,7 @@ void decode_project_impl(const Dims &d, const gta_weights &w, const T *x, int ba
                 EpiStoreF32{ws.praw, d.wtot, off}, st);
     off += wn[i];
   }
-  finalize_decode_kernel<T><<<grid1d((int64_t)batch * d.wtot), 256, 0, st>>>(d, ws.praw, batch, ws.q, ws.g,
+  finalize_decode_kernel<T><<<grid1d((int64_t)batch * d.wtot), 256, 0, st>>>(d, ws.praw, 1, batch, ws.q, ws.g,
                                                                             ws.oldlen, view_of(&cache, slots));
 }
 
@@ -547,6 +554,12 @@ void generic_decode_project(const Dims &d, const gta_weights &w, const void *x_n
                             const gta_cache &cache, const int32_t *slots, const DecodeWs &ws, hipStream_t st) {
   if (d.dtype == GTA_BF16) decode_project_impl<bf16>(d, w, (const bf16 *)x_new, batch, cache, slots, ws, st);
   else decode_project_impl<float>(d, w, (const float *)x_new, batch, cache, slots, ws, st);
+}
+
+void launch_finalize_decode_bf16(const Dims &d, const float *part, int nsum, int batch, const gta_cache &cache,
+                                 const int32_t *slots, const DecodeWs &ws, hipStream_t st) {
+  finalize_decode_kernel<bf16><<<grid1d((int64_t)batch * d.wtot), 256, 0, st>>>(d, part, nsum, batch, ws.q, ws.g,
+                                                                               ws.oldlen, view_of(&cache, slots));
 }
 
 void launch_cached_len(const gta_cache &cache, const int32_t *slots, int batch, int32_t *oldlen, hipStream_t st) {

@@ -44,7 +44,7 @@ PrefillWs carve_prefill(const Dims &d, bool tuned, bool with_wo, int batch, int6
                         int max_len, void *base);
 
 struct DecodeWs {
-  float *praw;             // [batch, wtot] raw fp32 projections of the new tokens
+  float *praw;             // [ksplit, batch, wtot] raw fp32 projections of the new tokens (split-K partials)
   float *q;                // [batch, wq_w] rotated queries
   float *g;                // [batch, wg_w] gate pre-activations
   float *part;             // [batch, splits, n_q, d_l + 2]  (acc[d_l], m, l)
@@ -77,6 +77,8 @@ void generic_out_proj_f32in(const Dims &d, const gta_weights &w, const float *O,
 
 void launch_attn_prefill_rowwise(const Dims &d, const void *q, const void *k, const void *c, const int32_t *cu,
                                  int batch, int64_t total, int max_len, void *L, hipStream_t st);
+void launch_finalize_decode_bf16(const Dims &d, const float *part, int nsum, int batch, const gta_cache &cache,
+                                 const int32_t *slots, const DecodeWs &ws, hipStream_t st);
 void launch_cached_len(const gta_cache &cache, const int32_t *slots, int batch, int32_t *oldlen, hipStream_t st);
 void generic_decode_attention(const Dims &d, const float *q, const int32_t *oldlen, const gta_cache &cache,
                               const int32_t *slots, int batch, int splits, float *part, hipStream_t st);

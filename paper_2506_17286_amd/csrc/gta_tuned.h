@@ -24,6 +24,9 @@ void launch_proj_gemm(const Dims &d, const gta_weights &w, const void *x, int M,
                       const gta_cache *cache, const int32_t *slots, int max_len, hipStream_t st);
 void launch_decoder_gemm(const Dims &d, const void *L, const void *wp, const void *g, void *out, int M,
                          hipStream_t st);
+int skinny_ksplit(const Dims &d, int M);
+void launch_skinny_proj(const Dims &d, const gta_weights &w, const void *x, int M, float *part, int ksplit,
+                        hipStream_t st);
 void launch_plain_gemm(const void *A, int64_t lda, int M, int N, int K, const void *B, void *C, hipStream_t st);
 
 // bf16 MFMA causal prefill attention (gta_prefill_bf16.hip)
