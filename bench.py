@@ -27,6 +27,16 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBPS = 8000.0        # MI355X HBM3E
 
+# HBM bytes per launch of the dominant kernels, recorded from `rocprofv3 --pmc FETCH_SIZE` and
+# `--pmc WRITE_SIZE` runs of this file scaled by the reading for calibration_copy_kernel
+# (profiles/bench_<workload>.txt hold the commands and the raw readings).  Counters cannot be
+# read from inside this process, so these are the last recorded values, not live ones.
+RECORDED_TRAFFIC_BYTES = {
+    ("decode_b8_32k_bf16", "decode_attn_kernel"): 537.23e6 + 4.21e6,
+    ("decode_b64_8k_bf16", "decode_attn_kernel"): 1075.38e6 + 4.21e6,
+    ("prefill_1b_bf16", "attn_prefill_kernel"): 226.62e6 + 67.12e6,
+}
+
 
 def _sync():
     import torch
@@ -104,7 +114,8 @@ def bench_decode(wl, steps, warmup, want_cpu_baseline):
     kbytes = cm.decode_cache_bytes(wl, [int(caches[0][2][0])] * wl.batch)
     res["roofline"] = {"kernel": "decode_attn_kernel", "bound": "hbm", "achieved": kbytes / ksec / 1e9,
                        "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": kbytes / ksec / 1e9 / PEAK_HBM_GBPS,
-                       "traffic": None, "us_per_launch": ksec * 1e6, "algorithmic_bytes_per_launch": kbytes}
+                       "traffic": RECORDED_TRAFFIC_BYTES.get((wl.name, "decode_attn_kernel")),
+                       "us_per_launch": ksec * 1e6, "algorithmic_bytes_per_launch": kbytes}
     if want_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline_decode(wl, w, x_np, caches[0])
     return res
@@ -155,7 +166,8 @@ def bench_prefill(wl, steps, warmup, want_cpu_baseline):
     ksec = _event_time(attn_only, max(steps, 10))
     res["roofline"] = {"kernel": "attn_prefill_kernel", "bound": "mfma", "achieved": fl["attn"] / ksec / 1e12,
                        "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": fl["attn"] / ksec / 1e12 / PEAK_BF16_TFLOPS,
-                       "traffic": None, "us_per_launch": ksec * 1e6, "algorithmic_flops_per_launch": fl["attn"]}
+                       "traffic": RECORDED_TRAFFIC_BYTES.get((wl.name, "attn_prefill_kernel")),
+                       "us_per_launch": ksec * 1e6, "algorithmic_flops_per_launch": fl["attn"]}
     if want_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline_prefill(wl, w, x_np, lens, cu)
     return res
@@ -223,6 +235,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--only", choices=["decode32k", "decode8k", "prefill"], default=None,
                     help="measure one workload only (profiling runs)")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run calibration_copy_kernel once on 512 MiB (reads 512 MiB, writes 512 MiB): "
+                         "the reference the FETCH_SIZE / WRITE_SIZE counters of a --pmc run are scaled by")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding): use --gpus 1", file=sys.stderr)
@@ -233,6 +248,12 @@ def main():
     B.load()   # fails loudly if the HIP library is not built
     torch.cuda.set_device(0)
     cpu = not args.no_cpu_baseline
+    if args.calibration_copy:
+        src = torch.ones(512 << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        B.gta_calibration_copy(src, dst, 512 << 20)
+        torch.cuda.synchronize()
+        del src, dst
     dec = pre = dec8 = None
     if args.only in (None, "decode32k"):
         dec = bench_decode(W.by_name("decode_b8_32k_bf16"), args.steps, args.warmup, cpu)

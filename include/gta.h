@@ -163,6 +163,11 @@ GTA_API int gta_decode_combine(const gta_config *cfg, const gta_cache *cache, co
                                int32_t batch, int32_t num_splits, void *workspace, size_t workspace_bytes,
                                float *l_out, void *hip_stream);
 
+/* Plain device-to-device copy of `bytes` (a multiple of 16) by one kernel that reads every byte of
+ * src once and writes every byte of dst once: the known-traffic reference that per-dispatch
+ * hardware counters of HBM bytes are calibrated against when profiling the kernels above. */
+GTA_API int gta_calibration_copy(const void *src, void *dst, int64_t bytes, void *hip_stream);
+
 /* Static string for a gta_status value. */
 GTA_API const char *gta_strerror(int code);
 

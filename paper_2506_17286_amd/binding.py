@@ -21,7 +21,7 @@ GTA_ERR_NULL, GTA_ERR_SHAPE, GTA_ERR_ALIGN, GTA_ERR_DTYPE = -1, -2, -3, -4
 GTA_ERR_UNSUPPORTED, GTA_ERR_WORKSPACE, GTA_ERR_HIP, GTA_ERR_CACHE_FULL = -5, -6, -7, -8
 
 EXPORTS = ["gta_workspace_bytes", "gta_prefill", "gta_decode", "gta_cache_append", "gta_strerror",
-           "gta_uses_tuned_kernels", "gta_prefill_attention", "gta_decode_attention", "gta_decode_combine"]
+           "gta_uses_tuned_kernels", "gta_prefill_attention", "gta_decode_attention", "gta_decode_combine", "gta_calibration_copy"]
 
 
 class gta_config(ctypes.Structure):
@@ -78,6 +78,8 @@ def load(path: Optional[str] = None) -> ctypes.CDLL:
     lib.gta_decode_attention.argtypes = [cfgp, vp, cp, vp, i32, i32, vp, sz, vp]
     lib.gta_decode_combine.restype = ctypes.c_int
     lib.gta_decode_combine.argtypes = [cfgp, cp, vp, i32, i32, vp, sz, vp, vp]
+    lib.gta_calibration_copy.restype = ctypes.c_int
+    lib.gta_calibration_copy.argtypes = [vp, vp, i64, vp]
     lib.gta_strerror.restype = ctypes.c_char_p
     lib.gta_strerror.argtypes = [ctypes.c_int]
     lib.gta_uses_tuned_kernels.restype = ctypes.c_int
@@ -203,6 +205,12 @@ def gta_decode_combine(cfg: gta_config, cache: gta_cache, slots, batch: int, num
                                    _stream(stream))
     if check:
         _check(rc, "gta_decode_combine")
+    return rc
+
+
+def gta_calibration_copy(src, dst, nbytes: int, stream=None) -> int:
+    rc = load().gta_calibration_copy(_ptr(src), _ptr(dst), nbytes, _stream(stream))
+    _check(rc, "gta_calibration_copy")
     return rc
 
 

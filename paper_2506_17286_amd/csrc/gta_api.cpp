@@ -277,6 +277,14 @@ int gta_decode_combine(const gta_config *cfg, const gta_cache *cache, const int3
   return check_launch();
 }
 
+int gta_calibration_copy(const void *src, void *dst, int64_t bytes, void *hip_stream) {
+  if (!src || !dst) return GTA_ERR_NULL;
+  if (bytes < 0 || bytes % 16) return GTA_ERR_SHAPE;
+  if (misaligned(src) || misaligned(dst)) return GTA_ERR_ALIGN;
+  if (bytes == 0) return GTA_OK;
+  return launch_calibration_copy(src, dst, bytes, (hipStream_t)hip_stream);
+}
+
 int gta_cache_append(const gta_config *cfg, const gta_cache *cache, const int32_t *slots, const void *k_new,
                      const void *c_new, const int32_t *cu_new, int32_t batch, int32_t max_new, void *hip_stream) {
   Dims d;

@@ -425,6 +425,14 @@ __global__ void append_commit_kernel(CacheView cv, const int32_t *cu_new, int ba
   else cv.seq_lens[slot] = p + n;
 }
 
+// Plain device-to-device copy in 16-byte words: the known-traffic reference that hardware
+// counters (bytes fetched / written per dispatch) are calibrated against.
+__global__ __launch_bounds__(256) void calibration_copy_kernel(const uint4 *__restrict__ src, uint4 *__restrict__ dst,
+                                                               int64_t nwords) {
+  for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < nwords; i += (int64_t)gridDim.x * blockDim.x)
+    dst[i] = src[i];
+}
+
 CacheView view_of(const gta_cache *c, const int32_t *slots) {
   CacheView v{};
   if (c) {
@@ -604,6 +612,11 @@ void generic_out_proj_f32in(const Dims &d, const gta_weights &w, const float *O,
   else
     launch_gemm(O, (int64_t)d.wg_w, 0, 1, (const float *)w.wo, (int64_t)d.H, 0, M, d.H, d.wg_w, 1,
                 EpiStoreT<float>{(float *)out, d.H}, st);
+}
+
+int launch_calibration_copy(const void *src, void *dst, int64_t bytes, hipStream_t st) {
+  calibration_copy_kernel<<<4096, 256, 0, st>>>((const uint4 *)src, (uint4 *)dst, bytes / 16);
+  return check_launch();
 }
 
 int generic_cache_append(const Dims &d, const gta_cache &cache, const int32_t *slots, const void *k_new,

@@ -84,6 +84,7 @@ void generic_decode_attention(const Dims &d, const float *q, const int32_t *oldl
                               const int32_t *slots, int batch, int splits, float *part, hipStream_t st);
 void generic_decode_combine(const Dims &d, const float *part, const int32_t *oldlen, int splits, int batch, float *L,
                             hipStream_t st);
+int launch_calibration_copy(const void *src, void *dst, int64_t bytes, hipStream_t st);
 void launch_rowmap(const int32_t *cu, int batch, int64_t total, int32_t *seq_id, int32_t *pos,
                    hipStream_t st);
 void launch_rope_table(float2 *tab, int max_pos, int dh, double base, hipStream_t st);
