@@ -17,6 +17,13 @@
 
 #include "gta_tuned.h"
 
+#ifdef GTA_PROBE   // phase timestamps for the standalone timing probe; never defined in the library build
+__device__ long long gta_phase[8][4096];
+#define GTA_PHASE(i) do { if (threadIdx.x == 0) gta_phase[i][blockIdx.x % 4096] = wall_clock64(); } while (0)
+#else
+#define GTA_PHASE(i)
+#endif
+
 namespace gta {
 namespace {
 
@@ -114,6 +121,192 @@ __device__ __forceinline__ void gemm_mainloop(const bf16 *__restrict__ A, int64_
   }
 }
 
+// ---- software-pipelined main loop for the big tiles --------------------------------------------
+// One wave per SIMD owns a 128-wide accumulator tile, so nothing but the wave's own instruction
+// stream can hide latencies.  The loop is therefore pipelined by hand on three levels:
+//   * operand fragments of k-step kk+1 are read from LDS while the MFMAs of step kk run (two
+//     fragment sets); the fragments of the next tile's first step are read during the last step;
+//   * k-tile kt+1 is written to the other LDS stage during steps 0..2 of tile kt, and the one
+//     workgroup barrier of the tile sits before the last step, whose MFMAs cover its skew;
+//   * global loads run two tiles ahead of the LDS writes (two staging register sets): the loads of
+//     tile kt+3 go out in steps 1..3, each into registers whose LDS write was issued one step before.
+// Every step is one scheduling region in which the memory instructions are dealt out between the
+// MFMAs (sched_group_barrier), so the matrix pipe always has the next MFMA queued and neither the
+// LDS nor the vector-memory queue sees a burst.
+// The last three k-tiles have nothing left to prefetch for the product; the caller may use the two
+// staging sets that become free for a `tail` prefetch of 16 + 16 sixteen-byte chunks per thread
+// (the decoder fetches its gate tile this way), which are handed back in r_tail0 / r_tail1.
+template <class T>
+struct PipeMap {
+  static constexpr int A_CPR = T::BK / 8, A_RPP = T::NT / A_CPR, A_PASSES = T::BM / A_RPP;
+  static constexpr int B_CPR = T::BN / 8, B_RPP = T::NT / B_CPR, B_PASSES = T::BK / B_RPP;
+  static constexpr int KSTEPS = T::BK / 16;
+  static_assert(T::BM % A_RPP == 0 && T::BK % B_RPP == 0 && A_PASSES == 8 && B_PASSES == 8, "staging");
+  static_assert(KSTEPS == 4, "the step schedule below is written for four k-steps per tile");
+};
+template <class T>
+struct PipeStage { u32x4 a[PipeMap<T>::A_PASSES], b[PipeMap<T>::B_PASSES]; };
+
+enum : int { SG_MFMA = 0x008, SG_VMEM_READ = 0x020, SG_DS_READ = 0x100, SG_DS_WRITE = 0x200 };
+
+// Schedule of one k-step: N_FRAG fragment reads of the next step go out one per MFMA, then N_W LDS
+// writes and N_G global loads are dealt out over the remaining MFMAs.
+template <int N_MFMA, int N_FRAG, int N_W, int N_G>
+__device__ __forceinline__ void deal_step() {
+  static_assert(N_MFMA > N_FRAG, "schedule");
+#pragma unroll
+  for (int i = 0; i < N_FRAG; ++i) {
+    __builtin_amdgcn_sched_group_barrier(SG_MFMA, 1, 0);
+    __builtin_amdgcn_sched_group_barrier(SG_DS_READ, 1, 0);
+  }
+  constexpr int rest = N_MFMA - N_FRAG;
+  constexpr int pw = (N_W + rest - 1) / rest, pg = (N_G + rest - 1) / rest;
+#pragma unroll
+  for (int i = 0; i < rest; ++i) {
+    __builtin_amdgcn_sched_group_barrier(SG_MFMA, 1, 0);
+    if constexpr (pw > 0) __builtin_amdgcn_sched_group_barrier(SG_DS_WRITE, pw, 0);
+    if constexpr (pg > 0) __builtin_amdgcn_sched_group_barrier(SG_VMEM_READ, pg, 0);
+  }
+  __builtin_amdgcn_sched_barrier(0);
+}
+
+// Tail prefetch hook: chunk i (0..15) of tail set `set` is at gbase() + off(set, i) (wave-uniform) +
+// thr_of(set, i) (per thread), all offsets in bytes.
+struct NoTail {
+  static constexpr bool active = false;
+  __device__ const char *gbase() const { return nullptr; }
+  __device__ unsigned off(int, int) const { return 0; }
+  __device__ unsigned thr_of(int, int) const { return 0; }
+};
+
+// `Abase` points at row m0 of the row operand; `Bbase` + `boff` (bytes, per thread) at k-row
+// tid / B_CPR of this thread's 8-column chunk of the weight operand.  K / BK must be even and >= 4.
+template <class T, class Tail>
+__device__ __forceinline__ void gemm_mainloop_pipe(const bf16 *__restrict__ Abase, int64_t lda, int rows_valid,
+                                                   const bf16 *__restrict__ Bbase, unsigned boff, int64_t ldb,
+                                                   int K, char *smem, f32x16 (&acc)[T::TN][T::TM],
+                                                   PipeStage<T> &r_tail0, PipeStage<T> &r_tail1, const Tail &tail) {
+  typedef PipeMap<T> P;
+  typedef PipeStage<T> Stage;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wn = wave % T::WGN, wm = wave / T::WGN;
+  const int a_c = tid % P::A_CPR, a_r = tid / P::A_CPR;
+  const int b_c = tid % P::B_CPR, b_r = tid / P::B_CPR;
+  // Addresses are a wave-uniform base plus ONE 32-bit per-thread offset.  Pass i of the row operand
+  // covers rows i * A_RPP + a_r; ip is the last pass that holds a valid row.  Passes before it use the
+  // full per-thread offset, pass ip and the (entirely invalid) passes after it use row ip * A_RPP +
+  // min(a_r, last valid row of that pass): valid rows map to themselves, the rest stay in bounds.
+  const int ip = (rows_valid - 1) / P::A_RPP;
+  const unsigned athr = (unsigned)(a_r * lda + a_c * 8) * 2u;
+  const unsigned athr_p = (unsigned)(min(a_r, rows_valid - 1 - ip * P::A_RPP) * lda + a_c * 8) * 2u;
+  const char *Ab = reinterpret_cast<const char *>(Abase);
+  const char *Bb = reinterpret_cast<const char *>(Bbase);
+  const int nk = K / T::BK;
+
+  struct Frags { bf16x8 x[T::TM], w[T::TN]; };
+  // The 16 loads / LDS writes of a tile are split in three parts (6, 6, 4): A passes with
+  // i % 3 == part, B passes with (i + 1) % 3 == part; part < 0 = all.
+  // Tiles past the end of K are clamped to the last one (redundant loads, in bounds), except that
+  // with a tail, tile nk+1 is tail set 0 and tile nk+2 tail set 1.  The choice is made with scalar
+  // bit masks, not branches, so that every k-step stays one scheduling region.
+  const unsigned a_pass_bytes = (unsigned)(P::A_RPP * lda * 2), b_pass_bytes = (unsigned)(P::B_RPP * ldb * 2);
+  auto gload_part = [&](Stage &r, int kt, int part) {
+    const bool tl = Tail::active && kt > nk;
+    const int set = kt > nk + 1 ? 1 : 0;
+    kt = min(kt, nk - 1);
+    const char *ak = Ab + (int64_t)kt * (T::BK * 2);
+    const char *bk = Bb + (int64_t)kt * T::BK * ldb * 2;
+    const char *abase = tl ? tail.gbase() : ak, *bbase = tl ? tail.gbase() : bk;
+#pragma unroll
+    for (int i = 0; i < P::A_PASSES; ++i)
+      if (part < 0 || i % 3 == part) {
+        const unsigned o_tile = (unsigned)min(i, ip) * a_pass_bytes, o_tail = tail.off(set, i);
+        const unsigned t_tile = i < ip ? athr : athr_p, t_tail = tail.thr_of(set, i);
+        r.a[i] = *reinterpret_cast<const u32x4 *>(abase + (tl ? o_tail : o_tile) + (tl ? t_tail : t_tile));
+      }
+#pragma unroll
+    for (int i = 0; i < P::B_PASSES; ++i)
+      if (part < 0 || (i + 1) % 3 == part) {
+        const unsigned o_tile = (unsigned)i * b_pass_bytes, o_tail = tail.off(set, P::A_PASSES + i);
+        const unsigned t_tail = tail.thr_of(set, P::A_PASSES + i);
+        r.b[i] = *reinterpret_cast<const u32x4 *>(bbase + (tl ? o_tail : o_tile) + (tl ? t_tail : boff));
+      }
+  };
+  const int a_st = a_r * T::A_PITCH + a_c * 16, b_st = T::A_BYTES + b_r * T::B_PITCH + b_c * 16;
+  auto sstore_part = [&](char *st, const Stage &r, int part) {
+#pragma unroll
+    for (int i = 0; i < P::A_PASSES; ++i)
+      if (part < 0 || i % 3 == part) *reinterpret_cast<u32x4 *>(st + a_st + i * P::A_RPP * T::A_PITCH) = r.a[i];
+#pragma unroll
+    for (int i = 0; i < P::B_PASSES; ++i)
+      if (part < 0 || (i + 1) % 3 == part)
+        *reinterpret_cast<u32x4 *>(st + b_st + i * P::B_RPP * T::B_PITCH) = r.b[i];
+  };
+  const int xoff = (wm * T::WM + (lane & 31)) * T::A_PITCH + (lane >> 5) * 16;
+  const int woff = T::A_BYTES + ((lane >> 5) * 8 + ((lane & 15) >> 2)) * T::B_PITCH +
+                   (wn * T::WN + ((lane >> 4) & 1) * 16 + (lane & 3) * 4) * 2;
+  auto load_frags = [&](Frags &f, const char *st, int kk) {
+#pragma unroll
+    for (int tm = 0; tm < T::TM; ++tm)
+      f.x[tm] = *reinterpret_cast<const bf16x8 *>(st + xoff + tm * 32 * T::A_PITCH + kk * 32);
+#pragma unroll
+    for (int tn = 0; tn < T::TN; ++tn) {
+      const char *wp = st + woff + kk * 16 * T::B_PITCH + tn * 64;
+      s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(wp));
+      s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(wp + 4 * T::B_PITCH));
+      s16x8 w8 = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+      f.w[tn] = __builtin_bit_cast(bf16x8, w8);
+    }
+  };
+  auto mma = [&](const Frags &f) {
+#pragma unroll
+    for (int tn = 0; tn < T::TN; ++tn)
+#pragma unroll
+      for (int tm = 0; tm < T::TM; ++tm)
+        acc[tn][tm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.w[tn], f.x[tm], acc[tn][tm], 0, 0, 0);
+  };
+  constexpr int N_MFMA = T::TM * T::TN, N_FRAG = T::TM + 2 * T::TN;
+
+  Stage &r0 = r_tail1, &r1 = r_tail0;   // tile t is staged in r(t & 1); the tail sets end up in r1, r0
+  Frags f0, f1;
+  gload_part(r0, 0, -1);
+  gload_part(r1, 1, -1);
+  sstore_part(smem, r0, -1);
+  gload_part(r0, 2, -1);
+  __syncthreads();
+  load_frags(f0, smem, 0);
+  __builtin_amdgcn_sched_barrier(0);
+
+  // tile kt is in `cur`; `rw` holds tile kt+1 and is refilled with tile kt+3 (or a tail set)
+  auto tile = [&](char *cur, char *nxt, Stage &rw, int kt) {
+    load_frags(f1, cur, 1);
+    sstore_part(nxt, rw, 0);
+    mma(f0);
+    deal_step<N_MFMA, N_FRAG, 6, 0>();
+    load_frags(f0, cur, 2);
+    sstore_part(nxt, rw, 1);
+    gload_part(rw, kt + 3, 0);
+    mma(f1);
+    deal_step<N_MFMA, N_FRAG, 6, 6>();
+    load_frags(f1, cur, 3);
+    sstore_part(nxt, rw, 2);
+    gload_part(rw, kt + 3, 1);
+    mma(f0);
+    deal_step<N_MFMA, N_FRAG, 4, 6>();
+    // tile kt+1 is complete and every wave is done reading `cur` once all waves pass this barrier
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    load_frags(f0, nxt, 0);
+    gload_part(rw, kt + 3, 2);
+    mma(f1);
+    deal_step<N_MFMA, N_FRAG, 0, 4>();
+  };
+  char *s0 = smem, *s1 = smem + T::STAGE;
+  for (int kt = 0; kt < nk; kt += 2) {
+    tile(s0, s1, r1, kt);
+    tile(s1, s0, r0, kt + 1);
+  }
+}
+
 template <class T>
 __device__ __forceinline__ void zero_acc(f32x16 (&acc)[T::TN][T::TM]) {
 #pragma unroll
@@ -142,6 +335,44 @@ __device__ __forceinline__ void tile_of_block(int ntn, int ntm, int &mt, int &nt
   nt = id % ntn;
 }
 
+// ---- epilogue of the 256 x 256 tile through LDS -------------------------------------------------
+// In the accumulator layout a lane owns 4 consecutive columns of one row, so direct stores would be
+// 8 bytes wide and scattered over 32 rows per instruction.  The tile is therefore rounded to bf16,
+// parked in LDS in output layout (row pitch 528 bytes) and written out with 16-byte stores in which
+// 32 consecutive lanes cover one 512-byte row segment.
+constexpr int kOutPitch = 256 * 2 + 16;
+
+template <class T>
+__device__ __forceinline__ int out_lds_offset(int tm, int tn, int rq) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wn = wave % T::WGN, wm = wave / T::WGN;
+  return (wm * T::WM + tm * 32 + (lane & 31)) * kOutPitch + (wn * T::WN + tn * 32 + rq * 8 + (lane >> 5) * 4) * 2;
+}
+
+template <class T>
+__device__ __forceinline__ void tile_to_lds(const f32x16 (&acc)[T::TN][T::TM], char *smem) {
+  static_assert(T::BM == 256 && T::BN == 256 && T::SMEM >= 256 * kOutPitch, "epilogue staging");
+#pragma unroll
+  for (int tm = 0; tm < T::TM; ++tm)
+#pragma unroll
+    for (int tn = 0; tn < T::TN; ++tn)
+#pragma unroll
+      for (int rq = 0; rq < 4; ++rq)
+        *reinterpret_cast<bf16x4 *>(smem + out_lds_offset<T>(tm, tn, rq)) =
+            pack4(acc[tn][tm][rq * 4], acc[tn][tm][rq * 4 + 1], acc[tn][tm][rq * 4 + 2], acc[tn][tm][rq * 4 + 3]);
+}
+
+// calls f(row, chunk, value) for every 16-byte chunk (8 columns) of the staged tile: 32 lanes per row
+template <class F>
+__device__ __forceinline__ void for_each_out_chunk(const char *smem, F f) {
+  const int r0 = threadIdx.x >> 5, ch = threadIdx.x & 31;
+#pragma unroll 4
+  for (int it = 0; it < 32; ++it) {
+    const int r = it * 8 + r0;
+    f(r, ch, *reinterpret_cast<const u32x4 *>(smem + r * kOutPitch + ch * 16));
+  }
+}
+
 // ------------------------------------------------------------------------------ projection
 constexpr int kHeadDim = 128;   // the RoPE epilogue is compiled for d_h = 128
 
@@ -166,8 +397,18 @@ __global__ __launch_bounds__(T::NT) void proj_gemm_kernel(ProjArgs a) {
   const int m0 = mt * T::BM;
   f32x16 acc[T::TN][T::TM];
   zero_acc<T>(acc);
-  gemm_mainloop<T>(a.x, a.lda, a.M, m0, a.w[seg], a.width[seg], n_glob, a.K, smem, acc);
+  GTA_PHASE(0);
+  if constexpr (T::TM == 4 && T::TN == 4) {
+    const int ldb = a.width[seg];
+    const unsigned boff = (unsigned)((threadIdx.x / (T::BN / 8)) * ldb + (threadIdx.x % (T::BN / 8)) * 8) * 2u;
+    PipeStage<T> t0, t1;
+    gemm_mainloop_pipe<T>(a.x + (int64_t)m0 * a.lda, a.lda, a.M - m0, a.w[seg] + n_glob, boff, ldb, a.K, smem, acc, t0, t1,
+                          NoTail{});
+  } else {
+    gemm_mainloop<T>(a.x, a.lda, a.M, m0, a.w[seg], a.width[seg], n_glob, a.K, smem, acc);
+  }
 
+  GTA_PHASE(1);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wn = wave % T::WGN, wm = wave / T::WGN;
   const int nw = n_glob + wn * T::WN;            // first column of this wave inside its segment
@@ -203,6 +444,7 @@ __global__ __launch_bounds__(T::NT) void proj_gemm_kernel(ProjArgs a) {
         }
       }
     }
+    if constexpr (T::TM == 4 && T::TN == 4) continue;   // stored below through LDS
     bf16 *drow = a.dst[seg] + (int64_t)m * width + nw;
     bf16 *crow = nullptr;
     if (cache) {
@@ -219,6 +461,37 @@ __global__ __launch_bounds__(T::NT) void proj_gemm_kernel(ProjArgs a) {
         *reinterpret_cast<bf16x4 *>(drow + n) = v;
         if (crow) *reinterpret_cast<bf16x4 *>(crow + n) = v;
       }
+  }
+  if constexpr (T::TM == 4 && T::TN == 4) {
+    GTA_PHASE(2);
+    __syncthreads();                 // every wave is done with the operand stages
+    tile_to_lds<T>(acc, smem);
+    // cache row of every tile row (or -1), looked up once and shared through LDS
+    int64_t *crow_of = reinterpret_cast<int64_t *>(smem + 256 * kOutPitch);
+    static_assert(T::SMEM >= 256 * kOutPitch + 256 * 8, "epilogue staging");
+    if (cache) {
+      const int m = m0 + (int)threadIdx.x;
+      int64_t cr = -1;
+      if (m < a.M) {
+        const int p = a.pos[m], b = a.seq_id[m];
+        const int slot = a.slots ? a.slots[b] : b;
+        if (slot >= 0 && slot < a.max_batch && p < a.max_seq) cr = (int64_t)slot * a.max_seq + p;
+      }
+      crow_of[threadIdx.x] = cr;
+    }
+    __syncthreads();
+    GTA_PHASE(3);
+    bf16 *dst = a.dst[seg] + n_glob;
+    for_each_out_chunk(smem, [&](int r, int ch, u32x4 v) {
+      const int m = m0 + r;
+      if (m >= a.M) return;
+      *reinterpret_cast<u32x4 *>(dst + (int64_t)m * width + ch * 8) = v;
+      if (cache) {
+        const int64_t cr = crow_of[r];
+        if (cr >= 0) *reinterpret_cast<u32x4 *>(cache + cr * width + n_glob + ch * 8) = v;
+      }
+    });
+    GTA_PHASE(4);
   }
 }
 
@@ -266,6 +539,97 @@ __global__ __launch_bounds__(T::NT) void decoder_gemm_kernel(DecoderArgs a) {
   }
 }
 
+// tail prefetch of the decoder: chunk (set*16 + i) of a thread is row (set*16 + i)*8 + tid/32 of the
+// gate tile (rows past the end of the matrix re-read the last valid one)
+struct GateTail {
+  static constexpr bool active = true;
+  const char *base; unsigned pass_bytes, thr, thr_p; int ip;   // ip: last 8-row pass with a valid row
+  __device__ const char *gbase() const { return base; }
+  __device__ unsigned off(int set, int i) const { return (unsigned)min(set * 16 + i, ip) * pass_bytes; }
+  __device__ unsigned thr_of(int set, int i) const { return set * 16 + i < ip ? thr : thr_p; }
+};
+
+// Two heads of one map group per 256-wide tile (they share the row operand L_g), pipelined main
+// loop.  The gate is applied to the fp32 accumulators: the gate tile is fetched with coalesced
+// 16-byte loads into LDS in output layout, every lane reads the pre-activations of its own
+// elements from there and puts the gated, rounded result back in the same place.
+template <class T, bool GATE>
+__global__ __launch_bounds__(T::NT) void decoder_pair_kernel(DecoderArgs a) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  int mt, nt;
+  tile_of_block(a.nh / 2, (a.M + T::BM - 1) / T::BM, mt, nt);
+  const int head = nt * 2, m0 = mt * T::BM;
+  f32x16 acc[T::TN][T::TM];
+  zero_acc<T>(acc);
+  GTA_PHASE(0);
+  const int64_t ldo = (int64_t)a.nh * a.dh;
+  const int col0 = head * a.dh;
+  // the gate tile (32 chunks of 16 bytes per thread: rows it*8 + tid/32, chunk tid%32) is fetched by
+  // the main loop's tail prefetch while the last two k-tiles are multiplied
+  const int r0 = threadIdx.x >> 5, ch = threadIdx.x & 31;
+  const int rows_valid = a.M - m0;
+  // pass `it` covers rows it*8 + tid/32; rows past the last valid one are clamped to it (their outputs
+  // are not stored)
+  const int rv = min(rows_valid, T::BM);
+  GateTail gate_tail;
+  gate_tail.base = reinterpret_cast<const char *>(a.g + (int64_t)m0 * ldo + col0);
+  gate_tail.pass_bytes = (unsigned)(8 * ldo * 2);
+  gate_tail.ip = (rv - 1) / 8;
+  gate_tail.thr = (unsigned)(r0 * ldo + ch * 8) * 2u;
+  gate_tail.thr_p = (unsigned)(min(r0, (rv - 1) % 8) * ldo + ch * 8) * 2u;
+  PipeStage<T> g0, g1;
+  {
+    const int b_c = threadIdx.x % (T::BN / 8), b_r = threadIdx.x / (T::BN / 8);
+    const int col = b_c * 8;   // columns [0,128) belong to `head`, [128,256) to `head + 1`
+    const unsigned boff = (unsigned)((col / 128) * a.dl * a.dh + b_r * a.dh + col % 128) * 2u;
+    const bf16 *Ab = a.L + (int64_t)m0 * a.ldl + (head / a.hpq) * a.dl, *Bb = a.wp + (int64_t)head * a.dl * a.dh;
+    if constexpr (GATE) gemm_mainloop_pipe<T>(Ab, a.ldl, rows_valid, Bb, boff, a.dh, a.dl, smem, acc, g0, g1, gate_tail);
+    else gemm_mainloop_pipe<T>(Ab, a.ldl, rows_valid, Bb, boff, a.dh, a.dl, smem, acc, g0, g1, NoTail{});
+  }
+  GTA_PHASE(1);
+  __syncthreads();
+  if constexpr (GATE) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      *reinterpret_cast<u32x4 *>(smem + ((i) * 8 + r0) * kOutPitch + ch * 16) = g0.a[i];
+      *reinterpret_cast<u32x4 *>(smem + ((8 + i) * 8 + r0) * kOutPitch + ch * 16) = g0.b[i];
+      *reinterpret_cast<u32x4 *>(smem + ((16 + i) * 8 + r0) * kOutPitch + ch * 16) = g1.a[i];
+      *reinterpret_cast<u32x4 *>(smem + ((24 + i) * 8 + r0) * kOutPitch + ch * 16) = g1.b[i];
+    }
+    __syncthreads();
+  }
+  GTA_PHASE(2);
+  // one row block (tm) at a time: all 16 gate reads of the block are issued before the first is used
+#pragma unroll
+  for (int tm = 0; tm < T::TM; ++tm) {
+    bf16x4 gz[T::TN][4];
+    if constexpr (GATE) {
+#pragma unroll
+      for (int tn = 0; tn < T::TN; ++tn)
+#pragma unroll
+        for (int rq = 0; rq < 4; ++rq) gz[tn][rq] = *reinterpret_cast<const bf16x4 *>(smem + out_lds_offset<T>(tm, tn, rq));
+    }
+#pragma unroll
+    for (int tn = 0; tn < T::TN; ++tn)
+#pragma unroll
+      for (int rq = 0; rq < 4; ++rq) {
+        float v[4] = {acc[tn][tm][rq * 4], acc[tn][tm][rq * 4 + 1], acc[tn][tm][rq * 4 + 2], acc[tn][tm][rq * 4 + 3]};
+        if constexpr (GATE) {
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+            v[i] *= __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * (float)gz[tn][rq][i]));
+        }
+        *reinterpret_cast<bf16x4 *>(smem + out_lds_offset<T>(tm, tn, rq)) = pack4(v[0], v[1], v[2], v[3]);
+      }
+  }
+  __syncthreads();
+  GTA_PHASE(3);
+  for_each_out_chunk(smem, [&](int r, int ch, u32x4 v) {
+    if (m0 + r < a.M) *reinterpret_cast<u32x4 *>(a.out + (int64_t)(m0 + r) * ldo + col0 + ch * 8) = v;
+  });
+  GTA_PHASE(4);
+}
+
 // ------------------------------------------------------------------------------ plain GEMM
 struct PlainArgs { const bf16 *A; int64_t lda; int M, N, K; const bf16 *B; bf16 *C; };
 
@@ -277,7 +641,22 @@ __global__ __launch_bounds__(T::NT) void plain_gemm_kernel(PlainArgs a) {
   const int m0 = mt * T::BM, n0 = nt * T::BN;
   f32x16 acc[T::TN][T::TM];
   zero_acc<T>(acc);
-  gemm_mainloop<T>(a.A, a.lda, a.M, m0, a.B, a.N, n0, a.K, smem, acc);
+  if constexpr (T::TM == 4 && T::TN == 4) {
+    const unsigned boff = (unsigned)((threadIdx.x / (T::BN / 8)) * a.N + (threadIdx.x % (T::BN / 8)) * 8) * 2u;
+    PipeStage<T> t0, t1;
+    gemm_mainloop_pipe<T>(a.A + (int64_t)m0 * a.lda, a.lda, a.M - m0, a.B + n0, boff, a.N, a.K, smem, acc, t0, t1, NoTail{});
+  } else {
+    gemm_mainloop<T>(a.A, a.lda, a.M, m0, a.B, a.N, n0, a.K, smem, acc);
+  }
+  if constexpr (T::TM == 4 && T::TN == 4) {
+    __syncthreads();
+    tile_to_lds<T>(acc, smem);
+    __syncthreads();
+    for_each_out_chunk(smem, [&](int r, int ch, u32x4 v) {
+      if (m0 + r < a.M) *reinterpret_cast<u32x4 *>(a.C + (int64_t)(m0 + r) * a.N + n0 + ch * 8) = v;
+    });
+    return;
+  }
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wn = wave % T::WGN, wm = wave / T::WGN;
 #pragma unroll
@@ -358,6 +737,8 @@ bool gemm_shapes_supported(const Dims &d) {
   // RoPE pairing is lane-local only if a wave tile (128 columns) holds whole heads
   if (d.dtype != GTA_BF16 || d.dh != 128) return false;
   if (d.H % 64 || d.dl % 64 || d.wq_w % 128 || d.wk_w % 128 || d.wc_w % 128 || d.wg_w % 128) return false;
+  // row offsets inside a 256-row tile are kept in 32 bits
+  if (d.H > (1 << 20) || (int64_t)d.nq * d.dl > (1 << 20) || d.wg_w > (1 << 20)) return false;
   return true;
 }
 
@@ -373,6 +754,7 @@ void launch_proj_gemm(const Dims &d, const gta_weights &w, const void *x, int M,
     a.w[i] = (const bf16 *)wm[i]; a.width[i] = wd[i]; a.dst[i] = (bf16 *)dst[i];
     if (wd[i] % 256) big = false;
   }
+  if (d.H % 128 || d.H < 256) big = false;   // the pipelined loop takes an even number (>= 4) of k-tiles
   a.seq_id = ws.seq_id; a.pos = ws.pos;
   a.rope = d.rope ? ws.rope : nullptr; a.max_len = max_len; a.dh = d.dh;
   if (cache) {
@@ -421,13 +803,18 @@ void launch_decoder_gemm(const Dims &d, const void *L, const void *wp, const voi
   a.L = (const bf16 *)L; a.ldl = (int64_t)d.nq * d.dl; a.M = M;
   a.wp = (const bf16 *)wp; a.dl = d.dl; a.dh = d.dh; a.hpq = d.hpq; a.nh = d.nh;
   a.g = (const bf16 *)g; a.gate = d.gate; a.out = (bf16 *)out;
+  if (d.dh == 128 && d.hpq % 2 == 0 && d.dl % 128 == 0 && d.dl >= 256) {
+    if (d.gate) launch<TileBig>(decoder_pair_kernel<TileBig, true>, a, (d.nh / 2) * ((M + 255) / 256), st);
+    else launch<TileBig>(decoder_pair_kernel<TileBig, false>, a, (d.nh / 2) * ((M + 255) / 256), st);
+    return;
+  }
   const int nt = d.nh * (d.dh / 128) * ((M + 255) / 256);
   launch<TileHead>(decoder_gemm_kernel<TileHead>, a, nt, st);
 }
 
 void launch_plain_gemm(const void *A, int64_t lda, int M, int N, int K, const void *B, void *C, hipStream_t st) {
   PlainArgs a{(const bf16 *)A, lda, M, N, K, (const bf16 *)B, (bf16 *)C};
-  if (N % 256 == 0) launch<TileBig>(plain_gemm_kernel<TileBig>, a, (N / 256) * ((M + 255) / 256), st);
+  if (N % 256 == 0 && K % 128 == 0 && K >= 256) launch<TileBig>(plain_gemm_kernel<TileBig>, a, (N / 256) * ((M + 255) / 256), st);
   else launch<TileHead>(plain_gemm_kernel<TileHead>, a, (N / 128) * ((M + 255) / 256), st);
 }
 
