@@ -3,18 +3,37 @@
 // group, output width d_l (normalised, bf16).  The value decoder runs afterwards as a GEMM.
 //
 // One workgroup = 256 queries of one (sequence, group) x 256 latent columns; each of its 8 waves
-// (two per SIMD, so one wave's softmax overlaps the other's MFMAs) owns 32 queries and the whole
-// column slice: the softmax statistics of a query live in one lane pair and nothing is exchanged
-// between waves.  Wider latents are covered by several workgroups that each recompute the scores.  Both products are computed transposed:
-//   S^T[key][query] = K . Q^T      (row operand: K tile from LDS, column operand: Q in registers)
+// (two per SIMD, so one wave's softmax runs in the shadow of the other's MFMAs) owns 32 queries
+// and the whole column slice (128 accumulator registers): the softmax statistics of a query live
+// in one lane pair and nothing is exchanged between waves.  Wider latents are covered by several
+// workgroups that each recompute the scores.  Both products are computed transposed:
+//   S^T[key][query] = K . Q^T      (row operand: K tile, column operand: Q tile, both from LDS)
 //   L^T[col][query] += C^T . P^T   (row operand: latent tile through the LDS transpose read,
 //                                   column operand: P straight from the S^T accumulator registers)
-// so P never leaves registers and the per-query scale is a per-lane scalar.  Online softmax runs
-// in the log2 domain with a lazy rescale: the running maximum is only raised when a new score
-// exceeds it by more than 2^8, which keeps the 128 accumulator registers untouched in most tiles.
+// so P never leaves registers and the per-query scale is a per-lane scalar.
+//
+// Online softmax runs in the log2 domain and is branch-free in the common case: the running
+// maximum of a query moves only when a block exceeds it by more than 2^8; the factor
+// exp2(m_old - m_new) always multiplies the row sum and reaches the 128 accumulator registers in a
+// rarely taken branch.  The lane pair of a query is reduced with v_permlane32_swap, P is packed
+// with v_cvt_pk_bf16_f32 and summed with v_dot2_f32_bf16 (so the row sum is the sum of the rounded
+// values the MFMA sees).
+//
+// Key/latent tiles of 32 rows go global -> registers -> LDS through three stages: the loads of a
+// tile are issued two tiles ahead and written to LDS one tile ahead of its use, one barrier per
+// tile.  The finished tile is rounded to bf16, parked in LDS in output layout and
+// written with 16-byte stores, 32 lanes per 512-byte row segment.
 #include <math.h>
 
 #include "gta_tuned.h"
+
+#ifndef ATTN_VAR
+#define ATTN_VAR 0
+#endif
+
+#ifdef GTA_PROBE
+__device__ long long gta_aphase[4][8192];
+#endif
 
 namespace gta {
 namespace {
@@ -22,57 +41,89 @@ namespace {
 typedef __bf16 bf16;
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(8))) short s16x8;
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 
-template <int DLW_, int BK_>
-struct AttnTile {
-  static constexpr int DH = 128, DLW = DLW_, BK = BK_, BQ = 256, NT = 512;
-  static constexpr int NDLB = DLW / 32;            // 32-column accumulator blocks per wave
-  static constexpr int NKB = BK / 32;              // 32-key score blocks per tile
+struct AT {
+  static constexpr int DH = 128, DLW = 256, BK = 32, BQ = 256, NT = 512, NDLB = DLW / 32, NSTAGE = 3;
   static constexpr int K_PITCH = DH * 2 + 16;      // 16 * odd: conflict-free 16-byte row reads
   static constexpr int C_PITCH = DLW * 2 + 64;     // == 64 mod 256: conflict-free transpose reads
   static constexpr int K_BYTES = BK * K_PITCH, C_BYTES = BK * C_PITCH, STAGE = K_BYTES + C_BYTES;
-  static constexpr int SMEM = 2 * STAGE;
-  static constexpr int K_PASSES = BK * (DH / 8) / NT, C_PASSES = BK * (DLW / 8) / NT;
-  static_assert(BK % 32 == 0 && DLW % 32 == 0 && K_PASSES >= 1 && C_PASSES >= 1, "tile");
+  static constexpr int Q_BYTES = BQ * K_PITCH;     // the workgroup's query tile, same row layout as K
+  static constexpr int OUT_PITCH = DLW * 2 + 16;
+  static constexpr int SMEM = NSTAGE * STAGE + Q_BYTES;
+  static constexpr int K_LOADS = BK * (DH / 8) / NT, C_LOADS = BK * (DLW / 8) / NT;   // 1, 2
+  static_assert(SMEM >= BQ * OUT_PITCH && SMEM <= 160 * 1024, "LDS budget");
 };
 
 struct AttnArgs {
   const bf16 *q, *k, *c;     // packed [total, n_q*d_h], [total, n_k*d_h], [total, n_c*d_l]
   bf16 *L;                   // [total, n_q*d_l]
   const int32_t *cu; int per_seq;
-  int nq, qpk, qpc, wq_w, wk_w, wc_w, dl, n_qtiles;
+  int nq, qpk, qpc, wq_w, wk_w, wc_w, dl, n_qtiles, ndlc, batch;
   float scale_log2e;
 };
 
 constexpr float kLazyThreshold = 8.0f;   // log2 units
 
-template <class T>
-__global__ __launch_bounds__(T::NT) void attn_prefill_kernel(AttnArgs a) {
+// maximum / sum over the lane pair (l, l + 32) that shares a query
+__device__ __forceinline__ float pair_max(float v) {
+  const u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float pair_sum(float v) {
+  const u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+__global__ __launch_bounds__(AT::NT) void attn_prefill_kernel(AttnArgs a) {
+  typedef AT T;
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, h = lane >> 5;
-  const int qt = a.n_qtiles - 1 - (int)blockIdx.x;      // longest (latest) query tiles first
-  const int g = blockIdx.y % a.nq, dlc = blockIdx.y / a.nq, b = blockIdx.z;
+  const int tid = threadIdx.x, lane = tid & 63, h = lane >> 5, ln = lane & 31;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: branches on it are scalar
+  // Workgroups are dispatched in id order and a query tile costs (tile index + 1) key tiles, so the
+  // tile index is the slowest digit of the id, longest first (list scheduling needs that to balance
+  // the CUs); the sequence is the fastest digit, so the 8 XCDs (ids round-robin) each work on few
+  // sequences and the workgroups of one XCD stream the same key range through its L2 in step.
+  const int per_qt = a.batch * a.nq * a.ndlc;
+  const int qt = a.n_qtiles - 1 - (int)blockIdx.x / per_qt;
+  const int rest = (int)blockIdx.x % per_qt;
+  const int b = rest % a.batch, g = (rest / a.batch) % a.nq, dlc = rest / (a.batch * a.nq);
   const int64_t start = a.cu ? a.cu[b] : (int64_t)b * a.per_seq;
   const int Tb = a.cu ? a.cu[b + 1] - a.cu[b] : a.per_seq;
   const int q0 = qt * T::BQ;
   if (q0 >= Tb) return;
+#ifdef GTA_PROBE
+  const int wgid = blockIdx.x;
+  if (tid == 0) { gta_aphase[0][wgid % 8192] = __builtin_amdgcn_s_memtime(); gta_aphase[1][wgid % 8192] = wall_clock64(); }
+#endif
   const int qw0 = q0 + wave * 32;                        // first query of this wave
-  const int myq = qw0 + (lane & 31);                     // this lane's query position
-  const bf16 *Kg = a.k + start * a.wk_w + (g / a.qpk) * T::DH;
-  const bf16 *Cg = a.c + start * a.wc_w + (g / a.qpc) * a.dl + dlc * T::DLW;
+  const int kend = min(q0 + T::BQ, Tb);                  // keys [0, kend) are visible to this tile
+  const int ntiles = (kend + T::BK - 1) / T::BK;
+  const int kend_w = qw0 < Tb ? min(qw0 + 32, Tb) : 0;   // keys [0, kend_w) are visible to this wave
+  const char *Kb = reinterpret_cast<const char *>(a.k + start * a.wk_w + (g / a.qpk) * T::DH);
+  const char *Cb = reinterpret_cast<const char *>(a.c + start * a.wc_w + (g / a.qpc) * a.dl + dlc * T::DLW);
+  const unsigned wk2 = a.wk_w * 2, wc2 = a.wc_w * 2;
 
-  // Q^T column operand: lane holds d = ks*16 + h*8 .. +8 of its query, for the 8 k-steps
-  bf16x8 qf[T::DH / 16];
+  // The query tile lives in LDS behind the three stages (row = query, same pitch as a K tile): the
+  // Q^T column operand of k-step ks is the 16-byte chunk d = ks*16 + h*8 .. +8 of the lane's query.
+  char *qs = smem + T::NSTAGE * T::STAGE;
   {
-    const bf16 *qp = a.q + (start + min(myq, Tb - 1)) * a.wq_w + g * T::DH + h * 8;
+    const bf16 *qg = a.q + start * a.wq_w + g * T::DH;
 #pragma unroll
-    for (int ks = 0; ks < T::DH / 16; ++ks) qf[ks] = *reinterpret_cast<const bf16x8 *>(qp + ks * 16);
+    for (int i = 0; i < T::BQ * (T::DH / 8) / T::NT; ++i) {
+      const int idx = tid + i * T::NT, row = idx >> 4, ch = idx & 15;
+      *reinterpret_cast<u32x4 *>(qs + row * T::K_PITCH + ch * 16) =
+          *reinterpret_cast<const u32x4 *>(qg + (int64_t)min(q0 + row, Tb - 1) * a.wq_w + ch * 8);
+    }
   }
+  const char *qfrag = qs + (wave * 32 + ln) * T::K_PITCH + h * 16;
+
   f32x16 acc[T::NDLB];
 #pragma unroll
   for (int i = 0; i < T::NDLB; ++i)
@@ -80,122 +131,201 @@ __global__ __launch_bounds__(T::NT) void attn_prefill_kernel(AttnArgs a) {
     for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
   float m_run = -INFINITY, l_run = 0.f;
 
-  const int kend = min(q0 + T::BQ, Tb);                  // keys [0, kend) are visible to this tile
-  const int ntiles = (kend + T::BK - 1) / T::BK;
-
-  // cooperative tile staging: global -> registers -> LDS
-  u32x4 rk[T::K_PASSES], rc[T::C_PASSES];
+  // cooperative tile staging: global -> registers -> LDS; rows past the sequence re-read its last row
+  // (such keys are in the future of every valid query and are masked)
+  u32x4 rk[T::K_LOADS], rc[T::C_LOADS];
+  const int k_row = tid >> 4, k_ch = tid & 15, c_row = tid >> 5, c_ch = tid & 31;
   auto gload = [&](int t) {
     const int j0 = t * T::BK;
 #pragma unroll
-    for (int i = 0; i < T::K_PASSES; ++i) {
-      const int idx = tid + i * T::NT, row = idx / (T::DH / 8), ch = idx % (T::DH / 8);
-      const int64_t j = min(j0 + row, Tb - 1);
-      rk[i] = *reinterpret_cast<const u32x4 *>(Kg + j * a.wk_w + ch * 8);
+    for (int i = 0; i < T::K_LOADS; ++i) {
+      const unsigned r = min(j0 + k_row + i * 32, Tb - 1);   // K_LOADS == 1
+      rk[i] = *reinterpret_cast<const u32x4 *>(Kb + (r * wk2 + k_ch * 16));
     }
 #pragma unroll
-    for (int i = 0; i < T::C_PASSES; ++i) {
-      const int idx = tid + i * T::NT, row = idx / (T::DLW / 8), ch = idx % (T::DLW / 8);
-      const int64_t j = min(j0 + row, Tb - 1);
-      rc[i] = *reinterpret_cast<const u32x4 *>(Cg + j * a.wc_w + ch * 8);
+    for (int i = 0; i < T::C_LOADS; ++i) {
+      const unsigned r = min(j0 + c_row + i * 16, Tb - 1);
+      rc[i] = *reinterpret_cast<const u32x4 *>(Cb + (r * wc2 + c_ch * 16));
     }
   };
   auto sstore = [&](char *st) {
 #pragma unroll
-    for (int i = 0; i < T::K_PASSES; ++i) {
-      const int idx = tid + i * T::NT, row = idx / (T::DH / 8), ch = idx % (T::DH / 8);
-      *reinterpret_cast<u32x4 *>(st + row * T::K_PITCH + ch * 16) = rk[i];
-    }
+    for (int i = 0; i < T::K_LOADS; ++i)
+      *reinterpret_cast<u32x4 *>(st + (k_row + i * 32) * T::K_PITCH + k_ch * 16) = rk[i];
 #pragma unroll
-    for (int i = 0; i < T::C_PASSES; ++i) {
-      const int idx = tid + i * T::NT, row = idx / (T::DLW / 8), ch = idx % (T::DLW / 8);
-      *reinterpret_cast<u32x4 *>(st + T::K_BYTES + row * T::C_PITCH + ch * 16) = rc[i];
-    }
+    for (int i = 0; i < T::C_LOADS; ++i)
+      *reinterpret_cast<u32x4 *>(st + T::K_BYTES + (c_row + i * 16) * T::C_PITCH + c_ch * 16) = rc[i];
   };
-  const int koff = (lane & 31) * T::K_PITCH + h * 16;
+  const int koff = ln * T::K_PITCH + h * 16;
   const int coff = T::K_BYTES + (4 * h + ((lane & 15) >> 2)) * T::C_PITCH + (((lane >> 4) & 1) * 16 + (lane & 3) * 4) * 2;
 
-  auto compute = [&](const char *st, int t) {
-    const int j0 = t * T::BK;
+  // scores S^T of one 32-key block (raw, unscaled)
+  auto scores = [&](const char *st, f32x16 &s) {
+    // two independent accumulation chains: a dependent MFMA would wait for the full pipeline latency
+    f32x16 s2;
 #pragma unroll
-    for (int kb = 0; kb < T::NKB; ++kb) {
-      const int jb = j0 + kb * 32;
-      if (jb > qw0 + 31) continue;                       // block entirely above this wave's diagonal
-      // scores S^T[key][query], fp32
-      f32x16 s;
+    for (int r = 0; r < 16; ++r) { s[r] = 0.f; s2[r] = 0.f; }
 #pragma unroll
-      for (int r = 0; r < 16; ++r) s[r] = 0.f;
+    for (int ks = 0; ks < T::DH / 16; ks += 2) {
+      const bf16x8 kf0 = *reinterpret_cast<const bf16x8 *>(st + koff + ks * 32);
+      const bf16x8 qf0 = *reinterpret_cast<const bf16x8 *>(qfrag + ks * 32);
+      const bf16x8 kf1 = *reinterpret_cast<const bf16x8 *>(st + koff + ks * 32 + 32);
+      const bf16x8 qf1 = *reinterpret_cast<const bf16x8 *>(qfrag + ks * 32 + 32);
+      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf0, qf0, s, 0, 0, 0);
+      s2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf1, qf1, s2, 0, 0, 0);
+    }
 #pragma unroll
-      for (int ks = 0; ks < T::DH / 16; ++ks) {
-        const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(st + koff + kb * 32 * T::K_PITCH + ks * 32);
-        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s, 0, 0, 0);
+    for (int r = 0; r < 16; ++r) s[r] += s2[r];
+  };
+  // keys after the lane's query are masked in a block that touches the diagonal
+  auto mask = [&](f32x16 &s, int jb) {
+    const int lim = qw0 + ln - jb;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int ko = 8 * (r >> 2) + 4 * h + (r & 3);
+      s[r] = ko > lim ? -INFINITY : s[r];
+    }
+  };
+  // softmax of one block: pn = exp2(scaled score - running maximum) as bf16 MFMA column operands
+  // (k-slot i of lane half h  <->  key 16*mm + 8*(i/4) + 4*h + i%4); m_run / l_run are updated and
+  // corr is the factor the accumulators still have to take before this block is added
+  auto softmax = [&](const f32x16 &s, bf16x8 (&pn)[2], float &corr) {
+    float bm = fmaxf(s[0], s[1]);
+#pragma unroll
+    for (int r = 2; r < 16; r += 2) bm = fmaxf(fmaxf(s[r], s[r + 1]), bm);   // v_max3
+    const float m_cand = pair_max(bm) * a.scale_log2e;
+    const float m_new = m_cand > m_run + kLazyThreshold ? fmaxf(m_run, m_cand) : m_run;
+    corr = __builtin_amdgcn_exp2f(m_run - m_new);
+    m_run = m_new;
+    const bf16x2 ones = {(bf16)1.0f, (bf16)1.0f};
+    float ps = 0.f;
+#pragma unroll
+    for (int mm = 0; mm < 2; ++mm)
+#pragma unroll
+      for (int i = 0; i < 8; i += 2) {
+        const float p0 = __builtin_amdgcn_exp2f(fmaf(s[mm * 8 + i], a.scale_log2e, -m_new));
+        const float p1 = __builtin_amdgcn_exp2f(fmaf(s[mm * 8 + i + 1], a.scale_log2e, -m_new));
+        bf16x2 pk;
+        pk[0] = (bf16)p0; pk[1] = (bf16)p1;
+        pn[mm][i] = pk[0]; pn[mm][i + 1] = pk[1];
+        ps = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, ps, false);   // the row sum uses the rounded values
       }
-      // log2-domain scores, causal mask (key <= query), block maximum per query
-      float bm = -INFINITY;
-      const bool diag = jb + 31 > qw0;
+    l_run = fmaf(l_run, corr, ps);
+  };
+  // L^T += C^T . P^T, latent tile rows read through the transpose load with the same key order
+  auto pv = [&](const char *st, const bf16x8 (&pf)[2]) {
+    // key half outermost: consecutive MFMAs go to different accumulators
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        float x = s[r] * a.scale_log2e;
-        if (diag) {
-          const int key = jb + 8 * (r >> 2) + 4 * h + (r & 3);
-          if (key > myq) x = -INFINITY;
-        }
-        s[r] = x;
-        bm = fmaxf(bm, x);
-      }
-      bm = fmaxf(bm, __shfl_xor(bm, 32, 64));
-      if (__any(bm > m_run + kLazyThreshold)) {          // raise the running maximum (rare)
-        const float m_new = fmaxf(m_run, bm);
-        const float corr = __builtin_amdgcn_exp2f(m_run - m_new);
-        m_run = m_new;
-        l_run *= corr;
-#pragma unroll
-        for (int i = 0; i < T::NDLB; ++i)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) acc[i][r] *= corr;
-      }
-      float ps = 0.f;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) { s[r] = __builtin_amdgcn_exp2f(s[r] - m_run); ps += s[r]; }
-      l_run += ps;
-      // P^T column operands: k-slot i of lane half h  <->  key 16*mm + 8*(i/4) + 4*h + i%4
-      bf16x8 pf[2];
-#pragma unroll
-      for (int mm = 0; mm < 2; ++mm)
-#pragma unroll
-        for (int i = 0; i < 8; ++i) pf[mm][i] = (bf16)s[mm * 8 + i];
-      // L^T += C^T . P^T, latent tile rows read through the transpose load with the same key order
+    for (int mm = 0; mm < 2; ++mm) {
 #pragma unroll
       for (int dlb = 0; dlb < T::NDLB; ++dlb) {
-#pragma unroll
-        for (int mm = 0; mm < 2; ++mm) {
-          const char *cp = st + coff + (kb * 32 + mm * 16) * T::C_PITCH + dlb * 64;
-          s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(cp));
-          s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(cp + 8 * T::C_PITCH));
-          s16x8 c8 = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-          acc[dlb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, c8), pf[mm], acc[dlb], 0, 0, 0);
-        }
+        const char *cp = st + coff + mm * 16 * T::C_PITCH + dlb * 64;
+        s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(cp));
+        s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(cp + 8 * T::C_PITCH));
+        s16x8 c8 = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        acc[dlb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, c8), pf[mm], acc[dlb], 0, 0, 0);
       }
     }
   };
 
+  // The waves of a workgroup meet at a barrier every tile and so run in phase: the overlap of softmax
+  // arithmetic and MFMAs has to come from each wave's own instruction stream.  Iteration t issues the
+  // score MFMAs of block t+1, then the map-times-latent MFMAs of block t with the softmax arithmetic
+  // of block t+1 dealt out between them.
+  // Stages: tile t+1 is read (scores) from `nxt`, tile t (latents) from `cur`, tile t+2 (loaded during
+  // iteration t-1) is written to `fre`, tile t+3 is loaded.
+  const int nb_w = (kend_w + 31) >> 5;   // blocks this wave needs: 0 .. nb_w-1
+  bf16x8 pf[2];
+  float corr = 1.f;
   gload(0);
   sstore(smem);
+  gload(1);
   __syncthreads();
-  for (int t = 0; t < ntiles; ++t) {
-    char *cur = smem + (t & 1) * T::STAGE;
-    char *nxt = smem + ((t & 1) ^ 1) * T::STAGE;
-    if (t + 1 < ntiles) gload(t + 1);
-    compute(cur, t);
-    if (t + 1 < ntiles) sstore(nxt);
+  if (nb_w > 0) {
+    f32x16 s;
+    scores(smem, s);
+    if (31 > qw0) mask(s, 0);
+    softmax(s, pf, corr);
+    corr = 1.f;   // the accumulators are still zero
+  }
+  sstore(smem + T::STAGE);
+  gload(2);
+  __syncthreads();
+  int cur = 0, nxt = T::STAGE, fre = 2 * T::STAGE;
+  auto rotate = [&]() {
+    const int tmp = cur;
+    cur = nxt; nxt = fre; fre = tmp;
+  };
+  auto rescale = [&]() {
+    if (__builtin_amdgcn_ballot_w64(corr != 1.f) != 0) {   // rare: the running maximum moved
+#pragma unroll
+      for (int i = 0; i < T::NDLB; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][r] *= corr;
+    }
+  };
+  // main part: blocks t and t+1 both lie entirely below this wave's diagonal, so the body has no
+  // branch after the rescale check and is one scheduling region: 24 MFMAs, 48 LDS reads and the
+  // softmax arithmetic are dealt out so that every MFMA finds its operands already read
+  const int t_main = min(nb_w, qw0 >> 5) - 1;   // iterations 0 .. t_main-1
+  int t = 0;
+#pragma unroll 1
+  for (; t < t_main; ++t) {
+    sstore(smem + fre);
+    gload(t + 3);
+    rescale();
+    f32x16 s;
+    bf16x8 pn[2];
+    scores(smem + nxt, s);
+    softmax(s, pn, corr);
+    pv(smem + cur, pf);
+    pf[0] = pn[0]; pf[1] = pn[1];
+    __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x002, 6, 0);
+    }
     __syncthreads();
+    rotate();
+  }
+  // the blocks around the diagonal, then idle iterations that only keep staging for the other waves
+#pragma unroll 1
+  for (; t < ntiles; ++t) {
+    sstore(smem + fre);
+    gload(t + 3);
+    if (t < nb_w) {
+      rescale();
+      f32x16 s;
+      bf16x8 pn[2];
+      if (t + 1 < nb_w) {
+        scores(smem + nxt, s);
+        if ((t + 1) * 32 + 31 > qw0) mask(s, (t + 1) * 32);
+      } else {   // no further block: all-masked scores leave the statistics unchanged and give P = 0
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s[r] = -INFINITY;
+      }
+      softmax(s, pn, corr);
+      pv(smem + cur, pf);
+      pf[0] = pn[0]; pf[1] = pn[1];
+    }
+    __syncthreads();
+    rotate();
   }
 
-  // normalise and store: lane owns query myq and 4 consecutive columns per (block, r/4)
-  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
-  if (myq < Tb) {
-    const float inv = 1.0f / l_tot;
-    bf16 *Lr = a.L + (start + myq) * (int64_t)(a.nq * a.dl) + g * a.dl + dlc * T::DLW + 4 * h;
+#ifdef GTA_PROBE
+  if (tid == 0) { gta_aphase[2][wgid % 8192] = __builtin_amdgcn_s_memtime(); gta_aphase[3][wgid % 8192] = wall_clock64(); }
+#endif
+  // ---- normalise, park the tile in LDS in output layout, write row-contiguous 16-byte chunks
+  {
+    const float inv = 1.0f / pair_sum(l_run);
+    const int row = wave * 32 + ln;
 #pragma unroll
     for (int dlb = 0; dlb < T::NDLB; ++dlb)
 #pragma unroll
@@ -203,16 +333,26 @@ __global__ __launch_bounds__(T::NT) void attn_prefill_kernel(AttnArgs a) {
         bf16x4 v;
 #pragma unroll
         for (int i = 0; i < 4; ++i) v[i] = (bf16)(acc[dlb][rq * 4 + i] * inv);
-        *reinterpret_cast<bf16x4 *>(Lr + dlb * 32 + rq * 8) = v;
+        *reinterpret_cast<bf16x4 *>(smem + row * T::OUT_PITCH + (dlb * 32 + rq * 8 + 4 * h) * 2) = v;
       }
+  }
+  __syncthreads();
+  bf16 *Lb = a.L + (start + q0) * (int64_t)(a.nq * a.dl) + g * a.dl + dlc * T::DLW;
+  const int r0 = tid >> 5, ch = tid & 31;
+#pragma unroll 4
+  for (int it = 0; it < 16; ++it) {
+    const int r = it * 16 + r0;
+    if (q0 + r < Tb)
+      *reinterpret_cast<u32x4 *>(Lb + (int64_t)r * (a.nq * a.dl) + ch * 8) =
+          *reinterpret_cast<const u32x4 *>(smem + r * T::OUT_PITCH + ch * 16);
   }
 }
 
-typedef AttnTile<256, 32> Attn256;
-
 }  // namespace
 
-bool attn_prefill_supported(const Dims &d) {
+bool attn_prefill_supported(const Dims &d, int max_len) {
+  // byte offsets inside one sequence's K / C rows are kept in 32 bits
+  if ((int64_t)max_len * d.wc_w * 2 >= ((int64_t)1 << 31) || (int64_t)max_len * d.wk_w * 2 >= ((int64_t)1 << 31)) return false;
   return d.dtype == GTA_BF16 && d.dh == 128 && d.dl % 256 == 0 && d.wk_w % 8 == 0 && d.wc_w % 8 == 0;
 }
 
@@ -222,16 +362,15 @@ void launch_attn_prefill_bf16(const Dims &d, const void *q, const void *k, const
   a.q = (const bf16 *)q; a.k = (const bf16 *)k; a.c = (const bf16 *)c; a.L = (bf16 *)L;
   a.cu = cu; a.per_seq = (int)(total / batch);
   a.nq = d.nq; a.qpk = d.qpk; a.qpc = d.qpc; a.wq_w = d.wq_w; a.wk_w = d.wk_w; a.wc_w = d.wc_w; a.dl = d.dl;
-  a.n_qtiles = (max_len + Attn256::BQ - 1) / Attn256::BQ;
+  a.n_qtiles = (max_len + AT::BQ - 1) / AT::BQ;
   a.scale_log2e = d.scale * 1.4426950408889634f;
   static bool attr_set = false;
   if (!attr_set) {
-    (void)hipFuncSetAttribute((const void *)attn_prefill_kernel<Attn256>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                              Attn256::SMEM);
+    (void)hipFuncSetAttribute((const void *)attn_prefill_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, AT::SMEM);
     attr_set = true;
   }
-  dim3 grid(a.n_qtiles, d.nq * (d.dl / Attn256::DLW), batch);
-  attn_prefill_kernel<Attn256><<<grid, Attn256::NT, Attn256::SMEM, st>>>(a);
+  a.ndlc = d.dl / AT::DLW; a.batch = batch;
+  attn_prefill_kernel<<<a.n_qtiles * a.ndlc * d.nq * batch, AT::NT, AT::SMEM, st>>>(a);
 }
 
 }  // namespace gta

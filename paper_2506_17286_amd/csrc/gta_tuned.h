@@ -30,7 +30,7 @@ void launch_skinny_proj(const Dims &d, const gta_weights &w, const void *x, int 
 void launch_plain_gemm(const void *A, int64_t lda, int M, int N, int K, const void *B, void *C, hipStream_t st);
 
 // bf16 MFMA causal prefill attention (gta_prefill_bf16.hip)
-bool attn_prefill_supported(const Dims &d);
+bool attn_prefill_supported(const Dims &d, int max_len);
 void launch_attn_prefill_bf16(const Dims &d, const void *q, const void *k, const void *c, const int32_t *cu,
                               int batch, int64_t total, int max_len, void *L, hipStream_t st);
 

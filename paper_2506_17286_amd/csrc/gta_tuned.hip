@@ -15,7 +15,7 @@ int tuned_prefill(const Dims &d, const gta_weights &w, const void *x, const int3
   launch_proj_gemm(d, w, x, M, ws, cache, slots, max_len, st);
   if (cache) launch_prefill_commit(*cache, slots, cu, batch, total, st);
   // Sec. 3.3: one causal softmax map per group applied to the latent values
-  if (attn_prefill_supported(d)) launch_attn_prefill_bf16(d, ws.q, ws.k, ws.c, cu, batch, total, max_len, ws.l, st);
+  if (attn_prefill_supported(d, max_len)) launch_attn_prefill_bf16(d, ws.q, ws.k, ws.c, cu, batch, total, max_len, ws.l, st);
   else launch_attn_prefill_rowwise(d, ws.q, ws.k, ws.c, cu, batch, total, max_len, ws.l, st);
   // Sec. 3.2 value decoder with the gate in the epilogue, then the optional W_O
   if (w.wo) {
