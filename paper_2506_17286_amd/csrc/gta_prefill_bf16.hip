@@ -161,21 +161,14 @@ __global__ __launch_bounds__(AT::NT) void attn_prefill_kernel(AttnArgs a) {
 
   // scores S^T of one 32-key block (raw, unscaled)
   auto scores = [&](const char *st, f32x16 &s) {
-    // two independent accumulation chains: a dependent MFMA would wait for the full pipeline latency
-    f32x16 s2;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) { s[r] = 0.f; s2[r] = 0.f; }
+    for (int r = 0; r < 16; ++r) s[r] = 0.f;
 #pragma unroll
-    for (int ks = 0; ks < T::DH / 16; ks += 2) {
-      const bf16x8 kf0 = *reinterpret_cast<const bf16x8 *>(st + koff + ks * 32);
-      const bf16x8 qf0 = *reinterpret_cast<const bf16x8 *>(qfrag + ks * 32);
-      const bf16x8 kf1 = *reinterpret_cast<const bf16x8 *>(st + koff + ks * 32 + 32);
-      const bf16x8 qf1 = *reinterpret_cast<const bf16x8 *>(qfrag + ks * 32 + 32);
-      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf0, qf0, s, 0, 0, 0);
-      s2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf1, qf1, s2, 0, 0, 0);
+    for (int ks = 0; ks < T::DH / 16; ++ks) {
+      const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(st + koff + ks * 32);
+      const bf16x8 qf = *reinterpret_cast<const bf16x8 *>(qfrag + ks * 32);
+      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf, s, 0, 0, 0);
     }
-#pragma unroll
-    for (int r = 0; r < 16; ++r) s[r] += s2[r];
   };
   // keys after the lane's query are masked in a block that touches the diagonal
   auto mask = [&](f32x16 &s, int jb) {
@@ -264,9 +257,7 @@ __global__ __launch_bounds__(AT::NT) void attn_prefill_kernel(AttnArgs a) {
         for (int r = 0; r < 16; ++r) acc[i][r] *= corr;
     }
   };
-  // main part: blocks t and t+1 both lie entirely below this wave's diagonal, so the body has no
-  // branch after the rescale check and is one scheduling region: 24 MFMAs, 48 LDS reads and the
-  // softmax arithmetic are dealt out so that every MFMA finds its operands already read
+  // main part: blocks t and t+1 both lie entirely below this wave's diagonal
   const int t_main = min(nb_w, qw0 >> 5) - 1;   // iterations 0 .. t_main-1
   int t = 0;
 #pragma unroll 1
@@ -275,23 +266,55 @@ __global__ __launch_bounds__(AT::NT) void attn_prefill_kernel(AttnArgs a) {
     gload(t + 3);
     rescale();
     f32x16 s;
-    bf16x8 pn[2];
     scores(smem + nxt, s);
-    softmax(s, pn, corr);
-    pv(smem + cur, pf);
-    pf[0] = pn[0]; pf[1] = pn[1];
-    __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);
-    }
+    __builtin_amdgcn_sched_barrier(0);
+    // 16 steps, each one MFMA of block t (latent fragment i, read two steps earlier), the transpose
+    // reads of fragment i+2 and a slice of the softmax arithmetic of block t+1; the scheduling barrier
+    // after every step pins this order, so each MFMA is followed by arithmetic that runs in its shadow
+    const char *st = smem + cur;
+    auto cread = [&](int i) {
+      const char *cp = st + coff + (i >> 3) * 16 * T::C_PITCH + (i & 7) * 64;
+      s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(cp));
+      s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(cp + 8 * T::C_PITCH));
+      s16x8 c8 = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+      return __builtin_bit_cast(bf16x8, c8);
+    };
+    bf16x8 cf[18], pn[2];
+    cf[0] = cread(0);
+    cf[1] = cread(1);
+    float b0, b1, b2, b3, b4, m_new = 0.f, negm = 0.f, ps = 0.f;
+    const bf16x2 ones = {(bf16)1.0f, (bf16)1.0f};
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x002, 6, 0);
+      if (i + 2 < 16) cf[i + 2] = cread(i + 2);
+      acc[i & 7] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cf[i], pf[i >> 3], acc[i & 7], 0, 0, 0);
+      if (i == 0) {
+        b0 = fmaxf(fmaxf(s[0], s[1]), s[2]); b1 = fmaxf(fmaxf(s[3], s[4]), s[5]); b2 = fmaxf(fmaxf(s[6], s[7]), s[8]);
+      } else if (i == 1) {
+        b3 = fmaxf(fmaxf(s[9], s[10]), s[11]); b4 = fmaxf(fmaxf(s[12], s[13]), s[14]); b0 = fmaxf(fmaxf(b0, b1), s[15]);
+      } else if (i == 2) {
+        b2 = fmaxf(fmaxf(b2, b3), b4);
+        b0 = pair_max(fmaxf(b0, b2));
+      } else if (i == 3) {
+        const float m_cand = b0 * a.scale_log2e;
+        m_new = m_cand > m_run + kLazyThreshold ? fmaxf(m_run, m_cand) : m_run;
+        corr = __builtin_amdgcn_exp2f(m_run - m_new);
+        m_run = m_new;
+        negm = -m_new;
+      } else if (i < 12) {
+        const int e = (i - 4) * 2;   // elements e, e+1 -> k-slots e%8, e%8+1 of pn[e/8]
+        const float p0 = __builtin_amdgcn_exp2f(fmaf(s[e], a.scale_log2e, negm));
+        const float p1 = __builtin_amdgcn_exp2f(fmaf(s[e + 1], a.scale_log2e, negm));
+        bf16x2 pk;
+        pk[0] = (bf16)p0; pk[1] = (bf16)p1;
+        pn[e >> 3][e & 7] = pk[0]; pn[e >> 3][(e & 7) + 1] = pk[1];
+        ps = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, ps, false);
+      } else if (i == 12) {
+        l_run = fmaf(l_run, corr, ps);
+      }
+      __builtin_amdgcn_sched_barrier(0);
     }
+    pf[0] = pn[0]; pf[1] = pn[1];
     __syncthreads();
     rotate();
   }
