@@ -256,9 +256,12 @@ int gta_decode_attention(const gta_config *cfg, const float *q, const gta_cache 
   if (!q) return GTA_ERR_NULL;
   if (misaligned(q)) return GTA_ERR_ALIGN;
   hipStream_t st = (hipStream_t)hip_stream;
-  launch_cached_len(*cache, slots, batch, ws.oldlen, st);
-  if (tuned_decode_supported(d)) tuned_decode_attention(d, q, ws.oldlen, *cache, slots, batch, ws.splits, ws.part, st);
-  else generic_decode_attention(d, q, ws.oldlen, *cache, slots, batch, ws.splits, ws.part, st);
+  if (tuned_decode_supported(d)) {
+    tuned_decode_attention(d, q, nullptr, ws.oldlen, *cache, slots, batch, ws.splits, ws.part, st);
+  } else {
+    launch_cached_len(*cache, slots, batch, ws.oldlen, st);
+    generic_decode_attention(d, q, ws.oldlen, *cache, slots, batch, ws.splits, ws.part, st);
+  }
   return check_launch();
 }
 

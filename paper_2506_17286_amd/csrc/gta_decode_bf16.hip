@@ -60,46 +60,74 @@ struct DecShape {
 
 constexpr int kWaves = 4;
 
+// Where the queries, the context lengths and (for a full decode step) the new token's key/latent row
+// come from:
+//   stage call     q_direct given, oldlen_in NULL: attend over the seq_lens[slot] cached rows as they are;
+//   pre-projected  q_direct and oldlen_in given:  the new row is already in the cache at oldlen_in[b];
+//   fused step     praw given: every workgroup sums the split-K partials of the projection for its
+//                  queries and rotates them at position seq_lens[slot] (App. B.1.1); the workgroup whose
+//                  slice ends at the new token also builds that token's key and latent rows, appends them
+//                  to the caches (App. B.1.3) and attends to them from LDS.
+struct RopeFreq { double f[64]; };   // base^(-2j/d_h), j < d_h/2 <= 64, computed on the host
+
+struct DecAttnArgs {
+  const float *q_direct;        // [batch, n_q*d_h] fp32, rotated, or NULL
+  const int32_t *oldlen_in;     // [batch] or NULL
+  const float *praw; int nsum, wtot, batch, rope;   // split-K partials [nsum, batch, wtot]
+  int32_t *oldlen_out;          // [batch] or NULL: index of the newest row that took part, or -1 (none / slot full)
+  bf16 *kc, *cc; const int32_t *seq_lens, *slots; int max_batch, max_seq;
+  int splits; float scale_log2e;
+  float *pacc, *pml;
+};
+
+// RoPE angle of position p and frequency f: reduced mod 2 pi in fp64, then fp32 sincos
+__device__ __forceinline__ void rope_sincos(int p, double f, float &sn, float &cs) {
+  const double ang = (double)p * f;
+  const double k = rint(ang * 0.15915494309189535);
+  double r = fma(-k, 6.283185307179586, ang);
+  r = fma(-k, 2.4492935982947064e-16, r);
+  sincosf((float)r, &sn, &cs);
+}
+
 template <class S>
-__global__ __launch_bounds__(256, S::OCC) void decode_attn_kernel(const float *__restrict__ Q, const int32_t *__restrict__ oldlen,
-                                                             const bf16 *__restrict__ kc, const bf16 *__restrict__ cc,
-                                                             const int32_t *__restrict__ slots, int max_seq, int splits,
-                                                             float scale_log2e, float *__restrict__ pacc,
-                                                             float *__restrict__ pml) {
+__global__ __launch_bounds__(256, S::OCC) void decode_attn_kernel(DecAttnArgs a, RopeFreq rf) {
   constexpr int DH = S::DH, QPK = S::QPK, NQ = S::NQ, QPC = S::QPC, DL = S::DL, KCH = S::KCH, CCH = S::CCH;
   constexpr int GPL = S::GPL, LPG = S::LPG, R = S::R, DLC = S::DLC;
   constexpr int KROW = S::NK * DH / 8, CROW = S::NC * DL / 8;   // 16-byte words per cache row
+  constexpr int WQ = NQ * DH, WK = S::NK * DH, WC = S::NC * DL;
   __shared__ float sm[kWaves][NQ], sl[kWaves][NQ];
   __shared__ float lacc[NQ * DL];
+  __shared__ float qs[WQ];                                       // rotated queries * scale * log2(e)
+  __shared__ __attribute__((aligned(16))) bf16 newrow[WK + WC];  // fused step: the new token's k | c row
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int s = blockIdx.x, b = blockIdx.y;
-  const int old = oldlen[b];
-  float *pa = pacc + (int64_t)(b * splits + s) * NQ * DL;
-  float *pm = pml + (int64_t)(b * splits + s) * NQ * 2;
-  if (old < 0) {   // slot full: the combine kernel zero-fills this sequence
+  const int s = blockIdx.x, b = blockIdx.y, splits = a.splits;
+  float *pa = a.pacc + (int64_t)(b * splits + s) * NQ * DL;
+  float *pm = a.pml + (int64_t)(b * splits + s) * NQ * 2;
+  const int slot = a.slots ? a.slots[b] : b;
+  const bool slot_ok = slot >= 0 && slot < a.max_batch;
+  // old = index of the newest row that takes part, n = old + 1 rows in all
+  int old;
+  if (a.oldlen_in) old = a.oldlen_in[b];
+  else if (a.praw) { const int p = slot_ok ? a.seq_lens[slot] : -1; old = (p >= 0 && p < a.max_seq) ? p : -1; }
+  else old = (slot_ok ? min(a.seq_lens[slot], a.max_seq) : 0) - 1;
+  if (a.oldlen_out && s == 0 && tid == 0) a.oldlen_out[b] = old;
+  if (old < 0 && (a.praw || a.oldlen_in)) {   // slot full: the tail kernel zero-fills this sequence
     if (tid < NQ) { pm[2 * tid] = -INFINITY; pm[2 * tid + 1] = 0.f; }
     return;
   }
   const int n = old + 1;
   int chunk = (n + splits - 1) / splits;
   chunk = (chunk + kWaves * R - 1) / (kWaves * R) * (kWaves * R);
-  const int j0 = min(n, s * chunk), j1 = min(n, j0 + chunk);
-  const int slot = slots ? slots[b] : b;
-  const u32x4 *Kp = reinterpret_cast<const u32x4 *>(kc + (int64_t)slot * max_seq * (S::NK * DH)) + lane;
-  const u32x4 *Cp = reinterpret_cast<const u32x4 *>(cc + (int64_t)slot * max_seq * (S::NC * DL)) + lane;
+  const int j0 = min(n, s * chunk);
+  int j1 = min(n, j0 + chunk);
+  // fused step: the new row (index old) is not in the cache yet; the workgroup whose slice holds it
+  // streams one row less and attends to the new row from LDS
+  const bool has_new = a.praw != nullptr && j0 < j1 && j1 == n;
+  if (has_new) j1 -= 1;
+  const u32x4 *Kp = reinterpret_cast<const u32x4 *>(a.kc + (int64_t)slot * a.max_seq * WK) + lane;
+  const u32x4 *Cp = reinterpret_cast<const u32x4 *>(a.cc + (int64_t)slot * a.max_seq * WC) + lane;
 
-  // this lane's slice of every query it scores against, pre-multiplied by scale * log2(e)
-  float qf[KCH][QPK][8];
-#pragma unroll
-  for (int i = 0; i < KCH; ++i)
-#pragma unroll
-    for (int u = 0; u < QPK; ++u) {
-      const int g = (i * GPL + lane / LPG) * QPK + u;
-      const float *qp = Q + (int64_t)b * (NQ * DH) + g * DH + (lane % LPG) * 8;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) qf[i][u][e] = qp[e] * scale_log2e;
-    }
   float m[KCH][QPK], l[KCH][QPK];
 #pragma unroll
   for (int i = 0; i < KCH; ++i)
@@ -113,7 +141,7 @@ __global__ __launch_bounds__(256, S::OCC) void decode_attn_kernel(const float *_
 #pragma unroll
       for (int e = 0; e < 8; ++e) acc[j][v][e] = 0.f;
 
-  const int nblk = (j1 - j0 + R - 1) / R;
+  const int nblk = (j1 - j0 + R - 1) / R;   // j1 - j0 may be 0 (only the new row)
   u32x4 kA[R][KCH], cA[R][CCH], kB[R][KCH], cB[R][CCH];
 
   auto load = [&](u32x4 (&kb)[R][KCH], u32x4 (&cb)[R][CCH], int blk) {
@@ -128,8 +156,87 @@ __global__ __launch_bounds__(256, S::OCC) void decode_attn_kernel(const float *_
     }
   };
 
-  auto compute = [&](const u32x4 (&kb)[R][KCH], const u32x4 (&cb)[R][CCH], int blk) {
-    const int nv = min(R, j1 - (j0 + blk * R));
+  // ---- queries (and the new row) into LDS.  Order of the requests: the partial sums of the queries
+  // first, then the first two blocks of the cache stream (which do not depend on the queries), so
+  // that the stream is already in flight while the queries are reduced and rotated.
+  constexpr int half = DH / 2;
+  constexpr int QPAIRS = WQ / 2 / 256;   // rotation pairs (e, e + d_h/2) of q per thread
+  static_assert(WQ % 512 == 0 && WK % 512 == 0 && WC % 256 == 0, "prologue mapping");
+  const int64_t pstride = (int64_t)a.batch * a.wtot;
+  const float *pb = a.praw ? a.praw + (int64_t)b * a.wtot : nullptr;
+  // sum over the split-K partials of column `c` (all loads independent, nsum <= 16)
+  auto col_sum = [&](int c) {
+    float pv[16];
+#pragma unroll
+    for (int k = 0; k < 16; ++k) pv[k] = k < a.nsum ? pb[k * pstride + c] : 0.f;
+    float v = 0.f;
+#pragma unroll
+    for (int k = 0; k < 16; ++k) v += pv[k];
+    return v;
+  };
+  auto rotate = [&](float &lo, float &hi, int j) {
+    if (!a.rope) return;
+    float sn, cs;
+    rope_sincos(old, rf.f[j], sn, cs);
+    const float l2 = lo * cs - hi * sn, h2 = hi * cs + lo * sn;
+    lo = l2; hi = h2;
+  };
+  float q_lo[QPAIRS], q_hi[QPAIRS];
+  if (a.praw) {
+#pragma unroll
+    for (int i = 0; i < QPAIRS; ++i) {
+      const int pr = tid + i * 256, c0 = (pr / half) * DH + pr % half;
+      q_lo[i] = col_sum(c0);
+      q_hi[i] = col_sum(c0 + half);
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < QPAIRS; ++i) {
+      const int pr = tid + i * 256, c0 = (pr / half) * DH + pr % half;
+      q_lo[i] = a.q_direct[(int64_t)b * WQ + c0];
+      q_hi[i] = a.q_direct[(int64_t)b * WQ + c0 + half];
+    }
+  }
+  __builtin_amdgcn_sched_barrier(0);   // keep the query loads ahead of the stream in the memory queue
+  if (wave < nblk) load(kA, cA, wave);
+  if (wave + kWaves < nblk) load(kB, cB, wave + kWaves);
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int i = 0; i < QPAIRS; ++i) {
+    const int pr = tid + i * 256, c0 = (pr / half) * DH + pr % half;
+    if (a.praw) rotate(q_lo[i], q_hi[i], pr % half);
+    qs[c0] = q_lo[i] * a.scale_log2e;
+    qs[c0 + half] = q_hi[i] * a.scale_log2e;
+  }
+  if (has_new) {   // the new token's key row (rotated) and latent row: LDS for this workgroup, cache for the rest
+    bf16 *krow = a.kc + ((int64_t)slot * a.max_seq + old) * WK, *crow = a.cc + ((int64_t)slot * a.max_seq + old) * WC;
+    for (int pr = tid; pr < WK / 2; pr += 256) {
+      const int c0 = (pr / half) * DH + pr % half;
+      float lo = col_sum(WQ + c0), hi = col_sum(WQ + c0 + half);
+      rotate(lo, hi, pr % half);
+      const bf16 rl = (bf16)lo, rh = (bf16)hi;
+      newrow[c0] = rl; newrow[c0 + half] = rh;
+      krow[c0] = rl; krow[c0 + half] = rh;
+    }
+    for (int c = tid; c < WC; c += 256) {
+      const bf16 r = (bf16)col_sum(WQ + WK + c);
+      newrow[WK + c] = r;
+      crow[c] = r;
+    }
+  }
+  __syncthreads();
+
+  // this lane's slice of every query it scores against
+  float qf[KCH][QPK][8];
+#pragma unroll
+  for (int i = 0; i < KCH; ++i)
+#pragma unroll
+    for (int u = 0; u < QPK; ++u) {
+      const int g = (i * GPL + lane / LPG) * QPK + u;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) qf[i][u][e] = qs[g * DH + (lane % LPG) * 8 + e];
+    }
+  auto compute = [&](const u32x4 (&kb)[R][KCH], const u32x4 (&cb)[R][CCH], int nv) {
     float p[R][KCH][QPK];
     // scores of R keys against this lane's groups (log2 domain)
 #pragma unroll
@@ -195,16 +302,27 @@ __global__ __launch_bounds__(256, S::OCC) void decode_attn_kernel(const float *_
   };
 
   // waves interleave blocks of R keys; two register buffers keep the next block in flight
+  auto nvalid = [&](int blk) { return min(R, j1 - (j0 + blk * R)); };
   int blk = wave;
-  if (blk < nblk) load(kA, cA, blk);
   while (blk < nblk) {
-    if (blk + kWaves < nblk) load(kB, cB, blk + kWaves);
-    compute(kA, cA, blk);
+    if (blk != wave && blk + kWaves < nblk) load(kB, cB, blk + kWaves);   // the first pair is already in flight
+    compute(kA, cA, nvalid(blk));
     blk += kWaves;
     if (blk >= nblk) break;
     if (blk + kWaves < nblk) load(kA, cA, blk + kWaves);
-    compute(kB, cB, blk);
+    compute(kB, cB, nvalid(blk));
     blk += kWaves;
+  }
+  if (has_new && wave == 0) {   // the new token's own row, from LDS: one more block with a single valid row
+    const u32x4 *nr = reinterpret_cast<const u32x4 *>(newrow) + lane;
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+#pragma unroll
+      for (int i = 0; i < KCH; ++i) kA[r][i] = nr[i * 64];
+#pragma unroll
+      for (int i = 0; i < CCH; ++i) cA[r][i] = nr[KROW + i * 64];
+    }
+    compute(kA, cA, 1);
   }
 
   // ---- merge the four waves (deterministic order), write the un-normalised partial
@@ -317,7 +435,8 @@ template <typename TO, int ROWS>
 __global__ __launch_bounds__(512) void decode_tail_kernel(Dims d, const float *__restrict__ pacc,
                                                           const float *__restrict__ pml,
                                                           const int32_t *__restrict__ oldlen, int splits, int batch,
-                                                          const float *__restrict__ G, const bf16 *__restrict__ wp,
+                                                          const float *__restrict__ G, int g_nsum, int64_t g_kstride, int g_ld,
+                                                          const bf16 *__restrict__ wp,
                                                           TO *__restrict__ out, int32_t *seq_lens, int32_t *status,
                                                           const int32_t *__restrict__ slots, int max_batch) {
   extern __shared__ float smem[];
@@ -326,6 +445,17 @@ __global__ __launch_bounds__(512) void decode_tail_kernel(Dims d, const float *_
   float *wt = red + max(8 * ROWS * d.dh, 2048);   // [ROWS][splits]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int head = blockIdx.x, g = head / d.hpq, b0 = blockIdx.y * ROWS;
+  // gate pre-activations of this thread's outputs = sum of the projection's split-K partials (one term
+  // if already summed); requested first, used last
+  constexpr int kMaxOut = (ROWS * 128 + 511) / 512;
+  float gz[kMaxOut];
+#pragma unroll
+  for (int o = 0; o < kMaxOut; ++o) {
+    gz[o] = 0.f;
+    const int i = tid + o * 512, r = i / d.dh, ee = i % d.dh;
+    if (d.gate && i < ROWS * d.dh && b0 + r < batch)
+      for (int k = 0; k < g_nsum; ++k) gz[o] += G[k * g_kstride + (int64_t)(b0 + r) * g_ld + head * d.dh + ee];
+  }
   if (head == 0 && tid < ROWS && b0 + tid < batch) {
     const int b = b0 + tid, slot = slots ? slots[b] : b;
     if (slot >= 0 && slot < max_batch) {
@@ -436,101 +566,176 @@ __global__ __launch_bounds__(512) void decode_tail_kernel(Dims d, const float *_
       for (int e = 0; e < 8; ++e) red[(wave * ROWS + r) * d.dh + cg * 8 + e] = z[r][e];
   }
   __syncthreads();
-  for (int i = tid; i < ROWS * d.dh; i += 512) {
+#pragma unroll
+  for (int o = 0; o < kMaxOut; ++o) {
+    const int i = tid + o * 512;
+    if (i >= ROWS * d.dh) break;
     const int r = i / d.dh, ee = i % d.dh, b = b0 + r;
     if (b >= batch) continue;
     float v = 0.f;
 #pragma unroll
     for (int q = 0; q < 8; ++q) v += red[(q * ROWS + r) * d.dh + ee];
     const int col = head * d.dh + ee;
-    if (d.gate) v *= 1.0f / (1.0f + __expf(-G[(int64_t)b * d.wg_w + col]));
+    if (d.gate) v *= 1.0f / (1.0f + __expf(-gz[o]));
     out[(int64_t)b * d.wg_w + col] = (TO)v;
   }
 }
 
+// The same tail for ONE sequence per workgroup (small batches), d_l = 512, d_h = 128 and at most 64
+// splits: every global load of the kernel -- split statistics, the 64 x 512 partial accumulators of
+// the group, the head's 512 x 128 decoder matrix, the gate terms -- is requested up front, so the
+// kernel costs one memory round trip instead of four dependent ones.
+template <typename TO>
+__global__ __launch_bounds__(512) void decode_tail1_kernel(Dims d, const float *__restrict__ pacc,
+                                                           const float *__restrict__ pml,
+                                                           const int32_t *__restrict__ oldlen, int splits,
+                                                           const float *__restrict__ G, int g_nsum, int64_t g_kstride,
+                                                           int g_ld, const bf16 *__restrict__ wp, TO *__restrict__ out,
+                                                           int32_t *seq_lens, int32_t *status,
+                                                           const int32_t *__restrict__ slots, int max_batch) {
+  constexpr int DL = 512, DH = 128, MAXS = 64;
+  __shared__ float wt[MAXS];
+  __shared__ float4 red4[4][DL / 4];
+  __shared__ float Ls[DL];
+  __shared__ float redz[8][DH];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int head = blockIdx.x, g = head / d.hpq, b = blockIdx.y;
+  const int old = oldlen[b];
+  const bool live = old >= 0;
+  // ---- all loads
+  float gz = 0.f;
+  if (d.gate && live && tid < DH)
+    for (int k = 0; k < g_nsum; ++k) gz += G[k * g_kstride + (int64_t)b * g_ld + head * DH + tid];
+  const int64_t ms = (int64_t)d.nq * 2;
+  float m_s = -INFINITY, l_s = 0.f;
+  if (live && tid < splits) {
+    const float *pm = pml + ((int64_t)b * splits * d.nq + g) * 2 + tid * ms;
+    m_s = pm[0]; l_s = pm[1];
+  }
+  const int c4 = tid & 127, ph = tid >> 7;
+  float4 v[MAXS / 4];
+  {
+    const float4 *pa = reinterpret_cast<const float4 *>(pacc + ((int64_t)b * splits * d.nq + g) * DL) + c4;
+    const int64_t as4 = (int64_t)d.nq * DL / 4;
+#pragma unroll
+    for (int u = 0; u < MAXS / 4; ++u) {
+      const int sp = ph + 4 * u;
+      v[u] = (live && sp < splits) ? pa[sp * as4] : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+  }
+  const int cg = tid & 15, aph = tid >> 4;   // 8 output columns, one of 32 latent phases
+  bf16x8 w8[DL / 32];
+  {
+    const bf16 *wb = wp + (int64_t)head * DL * DH + cg * 8;
+#pragma unroll
+    for (int i = 0; i < DL / 32; ++i) w8[i] = *reinterpret_cast<const bf16x8 *>(wb + (int64_t)(aph + 32 * i) * DH);
+  }
+  if (head == 0 && tid == 0) {
+    const int slot = slots ? slots[b] : b;
+    if (slot >= 0 && slot < max_batch) {
+      if (live) seq_lens[slot] = old + 1;
+      else status[slot] = GTA_ERR_CACHE_FULL;
+    }
+  }
+  // ---- log-sum-exp weights of the splits (wave 0)
+  if (wave == 0) {
+    float mx = m_s;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
+    const float e = m_s > -INFINITY ? exp2f(m_s - mx) : 0.f;
+    float ls = e * l_s;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) ls += __shfl_xor(ls, o, 64);
+    wt[lane] = e / ls;
+  }
+  __syncthreads();
+  // ---- combined, normalised group output
+  {
+    float4 acc4 = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+    for (int u = 0; u < MAXS / 4; ++u) {
+      const int sp = ph + 4 * u;
+      const float w = sp < splits ? wt[sp] : 0.f;
+      if (w != 0.f) {   // a split without rows has weight 0 and an unwritten accumulator
+        acc4.x = fmaf(w, v[u].x, acc4.x); acc4.y = fmaf(w, v[u].y, acc4.y);
+        acc4.z = fmaf(w, v[u].z, acc4.z); acc4.w = fmaf(w, v[u].w, acc4.w);
+      }
+    }
+    red4[ph][c4] = acc4;
+  }
+  __syncthreads();
+  if (tid < DL / 4) {
+    const float4 x0 = red4[0][tid], x1 = red4[1][tid], x2 = red4[2][tid], x3 = red4[3][tid];
+    Ls[tid * 4 + 0] = (x0.x + x1.x) + (x2.x + x3.x);
+    Ls[tid * 4 + 1] = (x0.y + x1.y) + (x2.y + x3.y);
+    Ls[tid * 4 + 2] = (x0.z + x1.z) + (x2.z + x3.z);
+    Ls[tid * 4 + 3] = (x0.w + x1.w) + (x2.w + x3.w);
+  }
+  __syncthreads();
+  // ---- value decoder (Sec. 3.2) from the prefetched matrix, gate, store
+  float z[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) z[e] = 0.f;
+#pragma unroll
+  for (int i = 0; i < DL / 32; ++i) {
+    const float lv = Ls[aph + 32 * i];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) z[e] = fmaf(lv, (float)w8[i][e], z[e]);
+  }
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    z[e] += __shfl_xor(z[e], 16, 64);
+    z[e] += __shfl_xor(z[e], 32, 64);
+  }
+  if (lane < 16) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) redz[wave][cg * 8 + e] = z[e];
+  }
+  __syncthreads();
+  if (tid < DH) {
+    float o = 0.f;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) o += redz[q][tid];
+    if (d.gate) o *= 1.0f / (1.0f + __expf(-gz));
+    out[(int64_t)b * d.wg_w + head * DH + tid] = live ? (TO)o : (TO)0.f;
+  }
+}
+
+// where the gate pre-activations come from: `nsum` terms at stride `kstride`, row pitch `ld`
+struct GateSrc { const float *g; int nsum; int64_t kstride; int ld; };
+
 template <typename TO, int ROWS>
-void launch_tail(const Dims &d, const float *pacc, const float *pml, const DecodeWs &ws, int batch, const bf16 *wp,
-                 TO *out, const gta_cache &cache, const int32_t *slots, hipStream_t st) {
+void launch_tail(const Dims &d, const float *pacc, const float *pml, const DecodeWs &ws, int batch, GateSrc gs,
+                 const bf16 *wp, TO *out, const gta_cache &cache, const int32_t *slots, hipStream_t st) {
   dim3 grid(d.nh, (batch + ROWS - 1) / ROWS);
   const size_t red = (size_t)(8 * ROWS * d.dh > 2048 ? 8 * ROWS * d.dh : 2048);
   const size_t smem = ((size_t)ROWS * d.dl + red + (size_t)ROWS * ws.splits) * sizeof(float);
-  decode_tail_kernel<TO, ROWS><<<grid, 512, smem, st>>>(d, pacc, pml, ws.oldlen, ws.splits, batch, ws.g, wp, out,
-                                                        cache.seq_lens, cache.status, slots, cache.max_batch);
+  decode_tail_kernel<TO, ROWS><<<grid, 512, smem, st>>>(d, pacc, pml, ws.oldlen, ws.splits, batch, gs.g, gs.nsum,
+                                                        gs.kstride, gs.ld, wp, out, cache.seq_lens, cache.status,
+                                                        slots, cache.max_batch);
 }
 
 template <typename TO>
-void launch_tail_any(const Dims &d, const float *pacc, const float *pml, const DecodeWs &ws, int batch,
+void launch_tail_any(const Dims &d, const float *pacc, const float *pml, const DecodeWs &ws, int batch, GateSrc gs,
                      const bf16 *wp, TO *out, const gta_cache &cache, const int32_t *slots, hipStream_t st) {
   // about 128 workgroups: one row per workgroup for small batches, up to 8 for large ones
   const int rows = batch * d.nh / 128;
-  if (rows >= 8) launch_tail<TO, 8>(d, pacc, pml, ws, batch, wp, out, cache, slots, st);
-  else if (rows >= 4) launch_tail<TO, 4>(d, pacc, pml, ws, batch, wp, out, cache, slots, st);
-  else if (rows >= 2) launch_tail<TO, 2>(d, pacc, pml, ws, batch, wp, out, cache, slots, st);
-  else launch_tail<TO, 1>(d, pacc, pml, ws, batch, wp, out, cache, slots, st);
-}
-
-// Sums the split-K partials of the new tokens' projections, rotates q and k at position
-// seq_lens[slot] (App. B.1.1; angle reduced mod 2 pi in fp64, then fp32 sincos), appends the key and
-// latent rows to the caches (App. B.1.3) and leaves q and the gate pre-activation in fp32.
-struct RopeFreq { double f[64]; };   // base^(-2j/d_h), j < d_h/2 <= 64, computed on the host
-
-__global__ __launch_bounds__(256) void decode_finalize_kernel(Dims d, RopeFreq rf, const float *__restrict__ part,
-                                                              int nsum, int batch, float *__restrict__ Qo,
-                                                              float *__restrict__ Go, int32_t *__restrict__ oldlen,
-                                                              bf16 *__restrict__ kc, bf16 *__restrict__ cc,
-                                                              const int32_t *__restrict__ seq_lens,
-                                                              const int32_t *__restrict__ slots, int max_batch,
-                                                              int max_seq) {
-  const int64_t idx = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
-  if (idx >= (int64_t)batch * d.wtot) return;
-  const int b = (int)(idx / d.wtot), col = (int)(idx % d.wtot);
-  const int slot = slots ? slots[b] : b;
-  const bool slot_ok = slot >= 0 && slot < max_batch;
-  const int p = slot_ok ? seq_lens[slot] : 0;
-  const bool ok = slot_ok && p >= 0 && p < max_seq;
-  if (col == 0) oldlen[b] = ok ? p : -1;
-  if (!ok) return;
-  const int64_t pstride = (int64_t)batch * d.wtot;
-  const int qk_w = d.wq_w + d.wk_w;
-  const int half = d.dh / 2, e = col % d.dh;
-  const bool rot = d.rope && col < qk_w;
-  const int64_t pidx = rot ? (e < half ? idx + half : idx - half) : idx;
-  // all partial loads are independent: issue them together (nsum <= 16)
-  float pv[16], pu[16];
-#pragma unroll
-  for (int s = 0; s < 16; ++s) {
-    pv[s] = s < nsum ? part[s * pstride + idx] : 0.f;
-    pu[s] = (rot && s < nsum) ? part[s * pstride + pidx] : 0.f;
+  if (rows < 2 && d.dl == 512 && d.dh == 128 && ws.splits <= 64) {
+    decode_tail1_kernel<TO><<<dim3(d.nh, batch), 512, 0, st>>>(d, pacc, pml, ws.oldlen, ws.splits, gs.g, gs.nsum,
+                                                               gs.kstride, gs.ld, wp, out, cache.seq_lens,
+                                                               cache.status, slots, cache.max_batch);
+    return;
   }
-  float v = 0.f, u = 0.f;
-#pragma unroll
-  for (int s = 0; s < 16; ++s) { v += pv[s]; u += pu[s]; }
-  if (rot) {
-    const double ang = (double)p * rf.f[e % half];
-    const double k = rint(ang * 0.15915494309189535);
-    double r = fma(-k, 6.283185307179586, ang);
-    r = fma(-k, 2.4492935982947064e-16, r);
-    float sn, cs;
-    sincosf((float)r, &sn, &cs);
-    v = e < half ? v * cs - u * sn : v * cs + u * sn;
-  }
-  if (col < d.wq_w) {
-    Qo[(int64_t)b * d.wq_w + col] = v;
-  } else if (col < qk_w) {
-    kc[((int64_t)slot * max_seq + p) * d.wk_w + (col - d.wq_w)] = (bf16)v;
-  } else if (col < qk_w + d.wc_w) {
-    cc[((int64_t)slot * max_seq + p) * d.wc_w + (col - qk_w)] = (bf16)v;
-  } else {
-    Go[(int64_t)b * d.wg_w + (col - qk_w - d.wc_w)] = v;
-  }
+  if (rows >= 8) launch_tail<TO, 8>(d, pacc, pml, ws, batch, gs, wp, out, cache, slots, st);
+  else if (rows >= 4) launch_tail<TO, 4>(d, pacc, pml, ws, batch, gs, wp, out, cache, slots, st);
+  else if (rows >= 2) launch_tail<TO, 2>(d, pacc, pml, ws, batch, gs, wp, out, cache, slots, st);
+  else launch_tail<TO, 1>(d, pacc, pml, ws, batch, gs, wp, out, cache, slots, st);
 }
 
 template <class S>
-void launch_attn(const Dims &d, const float *q, const int32_t *oldlen, const gta_cache &cache, const int32_t *slots,
-                 int batch, int splits, float *pacc, float *pml, hipStream_t st) {
-  dim3 grid(splits, batch);
-  decode_attn_kernel<S><<<grid, 256, 0, st>>>(q, oldlen, (const bf16 *)cache.k, (const bf16 *)cache.c, slots,
-                                             cache.max_seq, splits, d.scale * 1.4426950408889634f, pacc, pml);
+void launch_attn(const Dims &d, DecAttnArgs a, const RopeFreq &rf, int batch, hipStream_t st) {
+  dim3 grid(a.splits, batch);
+  decode_attn_kernel<S><<<grid, 256, 0, st>>>(a, rf);
 }
 
 typedef DecShape<128, 4, 1, 1, 1, 8, 2> Shape1B;      // 4 maps, 4 keys of 128, one latent of 512
@@ -548,12 +753,30 @@ bool tuned_decode_supported(const Dims &d) {
   return matches<Shape1B>(d) || matches<ShapeWide>(d);
 }
 
-void tuned_decode_attention(const Dims &d, const float *q, const int32_t *oldlen, const gta_cache &cache,
-                            const int32_t *slots, int batch, int splits, float *part, hipStream_t st) {
-  float *pacc = part;
-  float *pml = part + (int64_t)batch * splits * d.nq * d.dl;
-  if (matches<Shape1B>(d)) launch_attn<Shape1B>(d, q, oldlen, cache, slots, batch, splits, pacc, pml, st);
-  else launch_attn<ShapeWide>(d, q, oldlen, cache, slots, batch, splits, pacc, pml, st);
+static DecAttnArgs attn_args(const Dims &d, const gta_cache &cache, const int32_t *slots, int batch, int splits,
+                             float *part) {
+  DecAttnArgs a{};
+  a.batch = batch; a.wtot = d.wtot; a.rope = d.rope;
+  a.kc = (bf16 *)cache.k; a.cc = (bf16 *)cache.c; a.seq_lens = cache.seq_lens; a.slots = slots;
+  a.max_batch = cache.max_batch; a.max_seq = cache.max_seq;
+  a.splits = splits; a.scale_log2e = d.scale * 1.4426950408889634f;
+  a.pacc = part; a.pml = part + (int64_t)batch * splits * d.nq * d.dl;
+  return a;
+}
+
+static void launch_attn_any(const Dims &d, const DecAttnArgs &a, const RopeFreq &rf, int batch, hipStream_t st) {
+  if (matches<Shape1B>(d)) launch_attn<Shape1B>(d, a, rf, batch, st);
+  else launch_attn<ShapeWide>(d, a, rf, batch, st);
+}
+
+// q already rotated.  oldlen_in NULL: attend over the rows the caches hold now (stage call); otherwise
+// over rows 0 .. oldlen_in[b].  oldlen_out (may equal oldlen_in) receives the newest row index or -1.
+void tuned_decode_attention(const Dims &d, const float *q, const int32_t *oldlen_in, int32_t *oldlen_out,
+                            const gta_cache &cache, const int32_t *slots, int batch, int splits, float *part,
+                            hipStream_t st) {
+  DecAttnArgs a = attn_args(d, cache, slots, batch, splits, part);
+  a.q_direct = q; a.oldlen_in = oldlen_in; a.oldlen_out = oldlen_out;
+  launch_attn_any(d, a, RopeFreq{}, batch, st);
 }
 
 void tuned_decode_combine(const Dims &d, const float *part, const int32_t *oldlen, int splits, int batch, float *L,
@@ -565,27 +788,31 @@ void tuned_decode_combine(const Dims &d, const float *part, const int32_t *oldle
 
 int tuned_decode(const Dims &d, const gta_weights &w, const void *x_new, int batch, const gta_cache &cache,
                  const int32_t *slots, void *out, const DecodeWs &ws, hipStream_t st) {
-  // Sec. 3.2 projections of the new tokens, RoPE at position seq_len, append to the caches
+  // Three launches: split-K projection of the new tokens (Sec. 3.2); attention, whose workgroups sum
+  // the partials, rotate q and k at position seq_len and append the new rows themselves; the tail
+  // (combine, value decoder, gate from the same partials, bookkeeping).
+  GateSrc gs;
   if (gemm_shapes_supported(d)) {
     const int ks = skinny_ksplit(d, batch);
     launch_skinny_proj(d, w, x_new, batch, ws.praw, ks, st);
-    RopeFreq rf;
+    RopeFreq rf{};
     for (int j = 0; j < d.dh / 2; ++j) rf.f[j] = pow(d.rope_base, -2.0 * (double)j / (double)d.dh);
-    const int64_t n = (int64_t)batch * d.wtot;
-    decode_finalize_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(
-        d, rf, ws.praw, ks, batch, ws.q, ws.g, ws.oldlen, (bf16 *)cache.k, (bf16 *)cache.c, cache.seq_lens, slots,
-        cache.max_batch, cache.max_seq);
+    DecAttnArgs a = attn_args(d, cache, slots, batch, ws.splits, ws.part);
+    a.praw = ws.praw; a.nsum = ks; a.oldlen_out = ws.oldlen;
+    launch_attn_any(d, a, rf, batch, st);
+    gs = GateSrc{ws.praw + d.wq_w + d.wk_w + d.wc_w, ks, (int64_t)batch * d.wtot, d.wtot};
   } else {
     generic_decode_project(d, w, x_new, batch, cache, slots, ws, st);
+    tuned_decode_attention(d, ws.q, ws.oldlen, ws.oldlen, cache, slots, batch, ws.splits, ws.part, st);
+    gs = GateSrc{ws.g, 1, 0, d.wg_w};
   }
-  tuned_decode_attention(d, ws.q, ws.oldlen, cache, slots, batch, ws.splits, ws.part, st);
   const float *pacc = ws.part;
   const float *pml = ws.part + (int64_t)batch * ws.splits * d.nq * d.dl;
   if (w.wo) {
-    launch_tail_any<float>(d, pacc, pml, ws, batch, (const bf16 *)w.wp, ws.o, cache, slots, st);
+    launch_tail_any<float>(d, pacc, pml, ws, batch, gs, (const bf16 *)w.wp, ws.o, cache, slots, st);
     generic_out_proj_f32in(d, w, ws.o, batch, out, st);
   } else {
-    launch_tail_any<bf16>(d, pacc, pml, ws, batch, (const bf16 *)w.wp, (bf16 *)out, cache, slots, st);
+    launch_tail_any<bf16>(d, pacc, pml, ws, batch, gs, (const bf16 *)w.wp, (bf16 *)out, cache, slots, st);
   }
   return check_launch();
 }

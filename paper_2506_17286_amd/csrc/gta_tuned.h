@@ -13,8 +13,9 @@ int tuned_prefill(const Dims &d, const gta_weights &w, const void *x, const int3
 int tuned_decode(const Dims &d, const gta_weights &w, const void *x_new, int batch, const gta_cache &cache,
                  const int32_t *slots, void *out, const DecodeWs &ws, hipStream_t st);
 
-void tuned_decode_attention(const Dims &d, const float *q, const int32_t *oldlen, const gta_cache &cache,
-                            const int32_t *slots, int batch, int splits, float *part, hipStream_t st);
+void tuned_decode_attention(const Dims &d, const float *q, const int32_t *oldlen_in, int32_t *oldlen_out,
+                            const gta_cache &cache, const int32_t *slots, int batch, int splits, float *part,
+                            hipStream_t st);
 void tuned_decode_combine(const Dims &d, const float *part, const int32_t *oldlen, int splits, int batch, float *L,
                           hipStream_t st);
 
