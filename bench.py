@@ -55,15 +55,19 @@ def _time_steps(fn, steps, warmup):
 
 
 def _event_time(fn, reps):
-    """Average duration in seconds of fn() measured with HIP events on the current stream."""
+    """Average duration in seconds of one fn() launch: `reps` launches queued back to back between two
+    HIP events on the current stream (the launches overlap their own submission latency, so the
+    quotient is the kernel's duration plus the dispatch gap between consecutive kernels)."""
     import torch
-    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
     fn()
     _sync()
-    for a, b in evs:
-        a.record(); fn(); b.record()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(reps):
+        fn()
+    b.record()
     _sync()
-    return sum(a.elapsed_time(b) for a, b in evs) / reps * 1e-3
+    return a.elapsed_time(b) / reps * 1e-3
 
 
 def bench_decode(wl, steps, warmup, want_cpu_baseline):

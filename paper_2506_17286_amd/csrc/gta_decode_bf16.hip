@@ -117,10 +117,12 @@ __global__ __launch_bounds__(256, S::OCC) void decode_attn_kernel(DecAttnArgs a,
     return;
   }
   const int n = old + 1;
-  int chunk = (n + splits - 1) / splits;
-  chunk = (chunk + kWaves * R - 1) / (kWaves * R) * (kWaves * R);
-  const int j0 = min(n, s * chunk);
-  int j1 = min(n, j0 + chunk);
+  // balanced slices in units of R rows (the waves of a workgroup take blocks of R rows round-robin)
+  // In a fused step the last slice is made about 4 % shorter: its workgroup also builds the new row.
+  const int64_t units = (n + R - 1) / R;
+  const int64_t den = (int64_t)splits * 100 - (a.praw && splits > 1 ? 4 : 0);
+  const int j0 = min(n, (int)(units * s * 100 / den) * R);
+  int j1 = s + 1 == splits ? n : min(n, (int)(units * (s + 1) * 100 / den) * R);
   // fused step: the new row (index old) is not in the cache yet; the workgroup whose slice holds it
   // streams one row less and attends to the new row from LDS
   const bool has_new = a.praw != nullptr && j0 < j1 && j1 == n;
@@ -210,18 +212,29 @@ __global__ __launch_bounds__(256, S::OCC) void decode_attn_kernel(DecAttnArgs a,
   }
   if (has_new) {   // the new token's key row (rotated) and latent row: LDS for this workgroup, cache for the rest
     bf16 *krow = a.kc + ((int64_t)slot * a.max_seq + old) * WK, *crow = a.cc + ((int64_t)slot * a.max_seq + old) * WC;
-    for (int pr = tid; pr < WK / 2; pr += 256) {
-      const int c0 = (pr / half) * DH + pr % half;
-      float lo = col_sum(WQ + c0), hi = col_sum(WQ + c0 + half);
-      rotate(lo, hi, pr % half);
-      const bf16 rl = (bf16)lo, rh = (bf16)hi;
+    constexpr int KPAIRS = WK / 2 / 256, CCOLS = WC / 256;
+    float k_lo[KPAIRS], k_hi[KPAIRS], cv[CCOLS];   // all partial loads of the row are requested together
+#pragma unroll
+    for (int i = 0; i < KPAIRS; ++i) {
+      const int pr = tid + i * 256, c0 = (pr / half) * DH + pr % half;
+      k_lo[i] = col_sum(WQ + c0);
+      k_hi[i] = col_sum(WQ + c0 + half);
+    }
+#pragma unroll
+    for (int i = 0; i < CCOLS; ++i) cv[i] = col_sum(WQ + WK + tid + i * 256);
+#pragma unroll
+    for (int i = 0; i < KPAIRS; ++i) {
+      const int pr = tid + i * 256, c0 = (pr / half) * DH + pr % half;
+      rotate(k_lo[i], k_hi[i], pr % half);
+      const bf16 rl = (bf16)k_lo[i], rh = (bf16)k_hi[i];
       newrow[c0] = rl; newrow[c0 + half] = rh;
       krow[c0] = rl; krow[c0 + half] = rh;
     }
-    for (int c = tid; c < WC; c += 256) {
-      const bf16 r = (bf16)col_sum(WQ + WK + c);
-      newrow[WK + c] = r;
-      crow[c] = r;
+#pragma unroll
+    for (int i = 0; i < CCOLS; ++i) {
+      const bf16 r = (bf16)cv[i];
+      newrow[WK + tid + i * 256] = r;
+      crow[tid + i * 256] = r;
     }
   }
   __syncthreads();

@@ -774,7 +774,7 @@ int skinny_ksplit(const Dims &d, int M) {
   const int ktiles = d.H / 64;
   const int tiles = (d.wtot / 128) * ((M + 63) / 64);
   int want = (768 + tiles - 1) / tiles;
-  if (want > 16) want = 16;
+  if (want > 8) want = 8;
   int ks = 1;
   for (int c = 1; c <= want; ++c)
     if (ktiles % c == 0) ks = c;
