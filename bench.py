@@ -32,9 +32,9 @@ PEAK_HBM_GBPS = 8000.0        # MI355X HBM3E
 # (profiles/bench_<workload>.txt hold the commands and the raw readings).  Counters cannot be
 # read from inside this process, so these are the last recorded values, not live ones.
 RECORDED_TRAFFIC_BYTES = {
-    ("decode_b8_32k_bf16", "decode_attn_kernel"): 537.23e6 + 4.21e6,
-    ("decode_b64_8k_bf16", "decode_attn_kernel"): 1075.38e6 + 4.21e6,
-    ("prefill_1b_bf16", "attn_prefill_kernel"): 226.62e6 + 67.12e6,
+    ("decode_b8_32k_bf16", "decode_attn_kernel"): 537.79e6 + 4.22e6,
+    ("decode_b64_8k_bf16", "decode_attn_kernel"): 1079.08e6 + 4.26e6,
+    ("prefill_1b_bf16", "attn_prefill_kernel"): 93.64e6 + 67.11e6,
 }
 
 
@@ -186,8 +186,9 @@ def _blas_threads():
         return 1
 
 
-def cpu_baseline_decode(wl, w, x_np, cache0):
-    """The oracle's decode step on the same workload (all sequences), host cores of this machine."""
+def cpu_baseline_decode(wl, w, x_np, cache0, budget_s=12.0):
+    """The oracle's decode step on the same workload (every sequence), host cores of this machine; the
+    step is repeated until about `budget_s` seconds of oracle time have been spent."""
     import numpy as np
     import torch
     from oracle import gta_oracle as orc
@@ -196,39 +197,80 @@ def cpu_baseline_decode(wl, w, x_np, cache0):
                            wl.latent_dim, rope=wl.rope, rope_base=wl.rope_base)
     ow = orc.OracleWeights(w["wq"], w["wk"], w["wc"], w["wg"], w["wp"]).f64()
     k, c, seq = cache0[0], cache0[1], cache0[2]
-    nseq = min(wl.batch, 8)
+    seqs = []
+    for b in range(wl.batch):   # fp64 host copies, made once, outside the timed region
+        n = int(seq[b])
+        seqs.append((n, k[b:b + 1, :n + 1].to(torch.float64).cpu().numpy(), c[b:b + 1, :n + 1].to(torch.float64).cpu().numpy()))
     t = 0.0
     rows = 0
-    for b in range(nseq):
-        n = int(seq[b])
-        kc = k[b:b + 1, :n + 1].to(torch.float64).cpu().numpy()
-        cc = c[b:b + 1, :n + 1].to(torch.float64).cpu().numpy()
-        sl = np.array([n], dtype=np.int32); stt = np.zeros(1, dtype=np.int32)
-        t0 = time.perf_counter()
-        orc.decode(cfg, ow, x_np[b:b + 1], kc, cc, sl, stt, [0])
-        t += time.perf_counter() - t0
-        rows += n + 1
+    reps = 0
+    while t < budget_s and reps < 400:
+        for b, (n, kc, cc) in enumerate(seqs):
+            sl = np.array([n], dtype=np.int32); stt = np.zeros(1, dtype=np.int32)
+            t0 = time.perf_counter()
+            orc.decode(cfg, ow, x_np[b:b + 1], kc, cc, sl, stt, [0])
+            t += time.perf_counter() - t0
+            rows += n + 1
+        reps += 1
     by = cm.decode_cache_bytes(wl, [rows])
     return {"value": by / t / 1e9, "unit": "GB/s", "cores": _blas_threads(), "kind": "oracle",
-            "sample": f"oracle decode step of {nseq} of {wl.batch} sequences ({rows} cached rows, fp64 copies "
-                      f"of the same cache; bytes counted at the bf16 cache size), {t:.2f} s"}
+            "sample": f"oracle decode step of all {wl.batch} sequences, repeated {reps} times ({rows} cached rows in "
+                      f"all, fp64 copies of the same cache made outside the timed region; bytes counted at the "
+                      f"bf16 cache size), {t:.2f} s of oracle time"}
 
 
-def cpu_baseline_prefill(wl, w, x_np, lens, cu):
+def cpu_baseline_prefill(wl, w, x_np, lens, cu, budget_s=12.0):
+    """The oracle's prefill of whole sequences of the same workload until about `budget_s` seconds."""
     import numpy as np
     from oracle import gta_oracle as orc
     from paper_2506_17286_amd import costmodel as cm
     cfg = orc.OracleConfig(wl.d_model, wl.n_heads, wl.n_qgroups, wl.n_kgroups, wl.n_cgroups, wl.head_dim,
                            wl.latent_dim, rope=wl.rope, rope_base=wl.rope_base)
     ow = orc.OracleWeights(w["wq"], w["wk"], w["wc"], w["wg"], w["wp"]).f64()
-    T = int(lens[0])
-    t0 = time.perf_counter()
-    orc.prefill_sequence(cfg, ow, x_np[cu[0]:cu[1]])
-    t = time.perf_counter() - t0
-    fl = cm.prefill_flops(wl, [T])["total"]
+    t = 0.0
+    done = []
+    i = 0
+    while t < budget_s and i < 4 * wl.batch:
+        b = i % wl.batch
+        t0 = time.perf_counter()
+        orc.prefill_sequence(cfg, ow, x_np[cu[b]:cu[b + 1]])
+        t += time.perf_counter() - t0
+        done.append(int(lens[b]))
+        i += 1
+    fl = cm.prefill_flops(wl, done)["total"]
     return {"value": fl / t / 1e12, "unit": "TFLOP/s", "cores": _blas_threads(), "kind": "oracle",
-            "sample": f"oracle prefill of sequence 0 of {wl.batch} (T={T}, every row; algorithmic flops of that "
-                      f"sequence / wall time), {t:.2f} s"}
+            "sample": f"oracle prefill of {len(done)} whole sequences (the {wl.batch} of the workload, cycled; "
+                      f"T={done[0]}, every row; algorithmic flops of those sequences / wall time), {t:.2f} s"}
+
+
+def measured_ceilings():
+    """What this GPU sustains on kernels that do nothing but the bounding operation: a streaming read of
+    512 MiB and back-to-back bf16 MFMAs.  Context for the roofline fractions, which stay relative to
+    the published peaks."""
+    import torch
+    from paper_2506_17286_amd import binding as B
+    sink = torch.zeros(1024, dtype=torch.uint8, device="cuda")
+    nbytes = 512 << 20
+    bufs = [torch.ones(nbytes, dtype=torch.uint8, device="cuda") for _ in range(2)]
+    flip = [0]
+
+    def rd():
+        flip[0] ^= 1
+        B.gta_calibration_read(bufs[flip[0]], nbytes, 512, sink)
+
+    t_rd = _event_time(rd, 20)
+    del bufs
+    wgs, iters = 1024, 2000
+
+    def mm():
+        B.gta_calibration_mfma(wgs, iters, sink)
+
+    t_mm = _event_time(mm, 5)
+    fl = wgs * 4 * iters * 16 * 32768.0
+    return {"hbm_read_GBps": nbytes / t_rd / 1e9, "hbm_read_frac_of_peak": nbytes / t_rd / 1e9 / PEAK_HBM_GBPS,
+            "mfma_bf16_TFLOPs": fl / t_mm / 1e12, "mfma_bf16_frac_of_peak": fl / t_mm / 1e12 / PEAK_BF16_TFLOPS,
+            "what": "gta_calibration_read (512 MiB, 512 workgroups, non-temporal loads) and gta_calibration_mfma "
+                    "(1024 workgroups x 4 waves x 32000 v_mfma_f32_32x32x16_bf16, nothing else), timed here"}
 
 
 def main():
@@ -280,6 +322,7 @@ def main():
         line.update({"value": main_res["tflops"], "unit": "TFLOP/s", "ms_per_step": main_res["ms_per_step"],
                      "config": {"workload": main_res["workload"], "value_is": "algorithmic flops / whole gta_prefill call"}})
     line["roofline"] = main_res["roofline"]
+    line["measured_ceilings"] = measured_ceilings()
     if "cpu_baseline" in main_res:
         line["cpu_baseline"] = main_res.pop("cpu_baseline")
     if pre is not None and main_res is not pre:

@@ -168,6 +168,20 @@ GTA_API int gta_decode_combine(const gta_config *cfg, const gta_cache *cache, co
  * hardware counters of HBM bytes are calibrated against when profiling the kernels above. */
 GTA_API int gta_calibration_copy(const void *src, void *dst, int64_t bytes, void *hip_stream);
 
+/* Roofline calibration, not part of the attention pass: one kernel that only reads `bytes` of device
+ * memory at `src` once with non-temporal 16-byte loads, `workgroups` workgroups of 256 threads, each a
+ * contiguous slice (bytes must be a multiple of workgroups * 32768).  Timed by the caller, it gives
+ * the streaming-read rate the machine reaches next to the published HBM peak.  `sink` is device
+ * memory of at least 1 KiB that is (practically never) written.  GTA_ERR_SHAPE / _NULL / _ALIGN on
+ * misuse, nothing launched then. */
+GTA_API int gta_calibration_read(const void *src, int64_t bytes, int32_t workgroups, void *sink, void *hip_stream);
+
+/* Roofline calibration: `workgroups` workgroups of four waves, each wave issuing iters * 16
+ * v_mfma_f32_32x32x16_bf16 (32768 flop each) on 16 independent accumulators and nothing else.  Timed
+ * by the caller it gives the bf16 MFMA rate the chip sustains at the clock it holds under matrix load,
+ * next to the published 2.5 PFLOP/s.  `sink`: device memory of at least 1 KiB. */
+GTA_API int gta_calibration_mfma(int32_t workgroups, int32_t iters, void *sink, void *hip_stream);
+
 /* Static string for a gta_status value. */
 GTA_API const char *gta_strerror(int code);
 

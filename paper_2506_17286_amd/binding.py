@@ -21,7 +21,8 @@ GTA_ERR_NULL, GTA_ERR_SHAPE, GTA_ERR_ALIGN, GTA_ERR_DTYPE = -1, -2, -3, -4
 GTA_ERR_UNSUPPORTED, GTA_ERR_WORKSPACE, GTA_ERR_HIP, GTA_ERR_CACHE_FULL = -5, -6, -7, -8
 
 EXPORTS = ["gta_workspace_bytes", "gta_prefill", "gta_decode", "gta_cache_append", "gta_strerror",
-           "gta_uses_tuned_kernels", "gta_prefill_attention", "gta_decode_attention", "gta_decode_combine", "gta_calibration_copy"]
+           "gta_uses_tuned_kernels", "gta_prefill_attention", "gta_decode_attention", "gta_decode_combine", "gta_calibration_copy",
+           "gta_calibration_read", "gta_calibration_mfma"]
 
 
 class gta_config(ctypes.Structure):
@@ -80,6 +81,10 @@ def load(path: Optional[str] = None) -> ctypes.CDLL:
     lib.gta_decode_combine.argtypes = [cfgp, cp, vp, i32, i32, vp, sz, vp, vp]
     lib.gta_calibration_copy.restype = ctypes.c_int
     lib.gta_calibration_copy.argtypes = [vp, vp, i64, vp]
+    lib.gta_calibration_read.restype = ctypes.c_int
+    lib.gta_calibration_read.argtypes = [vp, i64, ctypes.c_int32, vp, vp]
+    lib.gta_calibration_mfma.restype = ctypes.c_int
+    lib.gta_calibration_mfma.argtypes = [ctypes.c_int32, ctypes.c_int32, vp, vp]
     lib.gta_strerror.restype = ctypes.c_char_p
     lib.gta_strerror.argtypes = [ctypes.c_int]
     lib.gta_uses_tuned_kernels.restype = ctypes.c_int
@@ -211,6 +216,18 @@ def gta_decode_combine(cfg: gta_config, cache: gta_cache, slots, batch: int, num
 def gta_calibration_copy(src, dst, nbytes: int, stream=None) -> int:
     rc = load().gta_calibration_copy(_ptr(src), _ptr(dst), nbytes, _stream(stream))
     _check(rc, "gta_calibration_copy")
+    return rc
+
+
+def gta_calibration_read(src, nbytes: int, workgroups: int, sink, stream=None) -> int:
+    rc = load().gta_calibration_read(_ptr(src), nbytes, workgroups, _ptr(sink), _stream(stream))
+    _check(rc, "gta_calibration_read")
+    return rc
+
+
+def gta_calibration_mfma(workgroups: int, iters: int, sink, stream=None) -> int:
+    rc = load().gta_calibration_mfma(workgroups, iters, _ptr(sink), _stream(stream))
+    _check(rc, "gta_calibration_mfma")
     return rc
 
 

@@ -288,6 +288,20 @@ int gta_calibration_copy(const void *src, void *dst, int64_t bytes, void *hip_st
   return launch_calibration_copy(src, dst, bytes, (hipStream_t)hip_stream);
 }
 
+int gta_calibration_read(const void *src, int64_t bytes, int32_t workgroups, void *sink, void *hip_stream) {
+  if (!src || !sink) return GTA_ERR_NULL;
+  if (workgroups <= 0 || workgroups > 65535 || bytes <= 0 || bytes % ((int64_t)workgroups * 256 * 8 * 16)) return GTA_ERR_SHAPE;
+  if (misaligned(src) || misaligned(sink)) return GTA_ERR_ALIGN;
+  return launch_calibration_read(src, bytes, workgroups, sink, (hipStream_t)hip_stream);
+}
+
+int gta_calibration_mfma(int32_t workgroups, int32_t iters, void *sink, void *hip_stream) {
+  if (!sink) return GTA_ERR_NULL;
+  if (workgroups <= 0 || workgroups > 65535 || iters <= 0) return GTA_ERR_SHAPE;
+  if (misaligned(sink)) return GTA_ERR_ALIGN;
+  return launch_calibration_mfma(workgroups, iters, sink, (hipStream_t)hip_stream);
+}
+
 int gta_cache_append(const gta_config *cfg, const gta_cache *cache, const int32_t *slots, const void *k_new,
                      const void *c_new, const int32_t *cu_new, int32_t batch, int32_t max_new, void *hip_stream) {
   Dims d;

@@ -433,6 +433,49 @@ __global__ __launch_bounds__(256) void calibration_copy_kernel(const uint4 *__re
     dst[i] = src[i];
 }
 
+// Streaming read of 16-byte words with non-temporal loads, one contiguous slice per workgroup: what
+// the memory system delivers to a kernel that does nothing else.  The xor of everything read goes to
+// `sink` only if it matches an arbitrary constant, so the loads cannot be dropped.
+typedef unsigned int cal_u32x4 __attribute__((ext_vector_type(4)));
+__global__ __launch_bounds__(256) void calibration_read_kernel(const cal_u32x4 *__restrict__ src, int64_t words_per_wg,
+                                                               uint32_t *sink) {
+  const cal_u32x4 *base = src + (int64_t)blockIdx.x * words_per_wg + threadIdx.x;
+  cal_u32x4 acc = {0u, 0u, 0u, 0u};
+  for (int64_t i = 0; i < words_per_wg; i += 256 * 8) {
+    cal_u32x4 v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = __builtin_nontemporal_load(base + i + u * 256);
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc ^= v[u];
+  }
+  if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9e3779b9u) sink[threadIdx.x] = acc.x;
+}
+
+// Nothing but v_mfma_f32_32x32x16_bf16 on 16 independent accumulators, four waves per CU (one per
+// SIMD): the rate the matrix pipes sustain at the clock the chip holds under that load.
+typedef __attribute__((ext_vector_type(8))) __bf16 cal_bf16x8;
+typedef __attribute__((ext_vector_type(16))) float cal_f32x16;
+__global__ __launch_bounds__(256) void calibration_mfma_kernel(int iters, float *sink) {
+  cal_bf16x8 x, y;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    x[i] = (__bf16)(0.001f * (float)((threadIdx.x * 7 + i) % 13) - 0.006f);
+    y[i] = (__bf16)(0.002f * (float)((threadIdx.x * 5 + i) % 11) - 0.01f);
+  }
+  cal_f32x16 acc[16];
+#pragma unroll
+  for (int t = 0; t < 16; ++t)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
+  for (int it = 0; it < iters; ++it)
+#pragma unroll
+    for (int t = 0; t < 16; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x, y, acc[t], 0, 0, 0);
+  float v = 0.f;
+#pragma unroll
+  for (int t = 0; t < 16; ++t) v += acc[t][0] + acc[t][15];
+  if (v == 123.456f) sink[threadIdx.x] = v;
+}
+
 CacheView view_of(const gta_cache *c, const int32_t *slots) {
   CacheView v{};
   if (c) {
@@ -612,6 +655,17 @@ void generic_out_proj_f32in(const Dims &d, const gta_weights &w, const float *O,
   else
     launch_gemm(O, (int64_t)d.wg_w, 0, 1, (const float *)w.wo, (int64_t)d.H, 0, M, d.H, d.wg_w, 1,
                 EpiStoreT<float>{(float *)out, d.H}, st);
+}
+
+int launch_calibration_read(const void *src, int64_t bytes, int workgroups, void *sink, hipStream_t st) {
+  const int64_t words_per_wg = bytes / 16 / workgroups;
+  calibration_read_kernel<<<workgroups, 256, 0, st>>>((const cal_u32x4 *)src, words_per_wg, (uint32_t *)sink);
+  return check_launch();
+}
+
+int launch_calibration_mfma(int workgroups, int iters, void *sink, hipStream_t st) {
+  calibration_mfma_kernel<<<workgroups, 256, 0, st>>>(iters, (float *)sink);
+  return check_launch();
 }
 
 int launch_calibration_copy(const void *src, void *dst, int64_t bytes, hipStream_t st) {
