@@ -7,7 +7,8 @@
 // and the whole column slice (128 accumulator registers): the softmax statistics of a query live
 // in one lane pair and nothing is exchanged between waves.  Wider latents are covered by several
 // workgroups that each recompute the scores.  Both products are computed transposed:
-//   S^T[key][query] = K . Q^T      (row operand: K tile, column operand: Q tile, both from LDS)
+//   S^T[key][query] = K . Q^T      (row operand: K tile from LDS, column operand: the wave's queries,
+//                                   held in 32 registers for the whole kernel)
 //   L^T[col][query] += C^T . P^T   (row operand: latent tile through the LDS transpose read,
 //                                   column operand: P straight from the S^T accumulator registers)
 // so P never leaves registers and the per-query scale is a per-lane scalar.
@@ -26,14 +27,6 @@
 #include <math.h>
 
 #include "gta_tuned.h"
-
-#ifndef ATTN_VAR
-#define ATTN_VAR 0
-#endif
-
-#ifdef GTA_PROBE
-__device__ long long gta_aphase[4][8192];
-#endif
 
 namespace gta {
 namespace {
@@ -54,9 +47,8 @@ struct AT {
   static constexpr int K_PITCH = DH * 2 + 16;      // 16 * odd: conflict-free 16-byte row reads
   static constexpr int C_PITCH = DLW * 2 + 64;     // == 64 mod 256: conflict-free transpose reads
   static constexpr int K_BYTES = BK * K_PITCH, C_BYTES = BK * C_PITCH, STAGE = K_BYTES + C_BYTES;
-  static constexpr int Q_BYTES = BQ * K_PITCH;     // the workgroup's query tile, same row layout as K
   static constexpr int OUT_PITCH = DLW * 2 + 16;
-  static constexpr int SMEM = NSTAGE * STAGE + Q_BYTES;
+  static constexpr int SMEM = BQ * OUT_PITCH > NSTAGE * STAGE ? BQ * OUT_PITCH : NSTAGE * STAGE;
   static constexpr int K_LOADS = BK * (DH / 8) / NT, C_LOADS = BK * (DLW / 8) / NT;   // 1, 2
   static_assert(SMEM >= BQ * OUT_PITCH && SMEM <= 160 * 1024, "LDS budget");
 };
@@ -90,18 +82,19 @@ __global__ __launch_bounds__(AT::NT) void attn_prefill_kernel(AttnArgs a) {
   // tile index is the slowest digit of the id, longest first (list scheduling needs that to balance
   // the CUs); the sequence is the fastest digit, so the 8 XCDs (ids round-robin) each work on few
   // sequences and the workgroups of one XCD stream the same key range through its L2 in step.
+  // Ids go to the XCDs round-robin whatever their cost, so with ragged lengths a fixed sequence digit
+  // would tie each sequence to one XCD and the longest sequences would bound the launch: the
+  // sequence digit is rotated by one per tile level, which spreads every sequence over all XCDs.
   const int per_qt = a.batch * a.nq * a.ndlc;
-  const int qt = a.n_qtiles - 1 - (int)blockIdx.x / per_qt;
+  const int lvl = (int)blockIdx.x / per_qt;
+  const int qt = a.n_qtiles - 1 - lvl;
   const int rest = (int)blockIdx.x % per_qt;
-  const int b = rest % a.batch, g = (rest / a.batch) % a.nq, dlc = rest / (a.batch * a.nq);
+  const int b = a.cu ? (rest % a.batch + lvl) % a.batch : rest % a.batch;
+  const int g = (rest / a.batch) % a.nq, dlc = rest / (a.batch * a.nq);
   const int64_t start = a.cu ? a.cu[b] : (int64_t)b * a.per_seq;
   const int Tb = a.cu ? a.cu[b + 1] - a.cu[b] : a.per_seq;
   const int q0 = qt * T::BQ;
   if (q0 >= Tb) return;
-#ifdef GTA_PROBE
-  const int wgid = blockIdx.x;
-  if (tid == 0) { gta_aphase[0][wgid % 8192] = __builtin_amdgcn_s_memtime(); gta_aphase[1][wgid % 8192] = wall_clock64(); }
-#endif
   const int qw0 = q0 + wave * 32;                        // first query of this wave
   const int kend = min(q0 + T::BQ, Tb);                  // keys [0, kend) are visible to this tile
   const int ntiles = (kend + T::BK - 1) / T::BK;
@@ -110,19 +103,15 @@ __global__ __launch_bounds__(AT::NT) void attn_prefill_kernel(AttnArgs a) {
   const char *Cb = reinterpret_cast<const char *>(a.c + start * a.wc_w + (g / a.qpc) * a.dl + dlc * T::DLW);
   const unsigned wk2 = a.wk_w * 2, wc2 = a.wc_w * 2;
 
-  // The query tile lives in LDS behind the three stages (row = query, same pitch as a K tile): the
-  // Q^T column operand of k-step ks is the 16-byte chunk d = ks*16 + h*8 .. +8 of the lane's query.
-  char *qs = smem + T::NSTAGE * T::STAGE;
+  // The wave's queries stay in registers for the whole kernel: the Q^T column operand of k-step ks is
+  // the 16-byte chunk d = ks*16 + h*8 .. +8 of the lane's query (rows past the sequence re-read its
+  // last row; their output is never written).
+  bf16x8 qf[T::DH / 16];
   {
-    const bf16 *qg = a.q + start * a.wq_w + g * T::DH;
+    const bf16 *qg = a.q + (start + min(qw0 + ln, Tb - 1)) * a.wq_w + g * T::DH + h * 8;
 #pragma unroll
-    for (int i = 0; i < T::BQ * (T::DH / 8) / T::NT; ++i) {
-      const int idx = tid + i * T::NT, row = idx >> 4, ch = idx & 15;
-      *reinterpret_cast<u32x4 *>(qs + row * T::K_PITCH + ch * 16) =
-          *reinterpret_cast<const u32x4 *>(qg + (int64_t)min(q0 + row, Tb - 1) * a.wq_w + ch * 8);
-    }
+    for (int ks = 0; ks < T::DH / 16; ++ks) qf[ks] = *reinterpret_cast<const bf16x8 *>(qg + ks * 16);
   }
-  const char *qfrag = qs + (wave * 32 + ln) * T::K_PITCH + h * 16;
 
   f32x16 acc[T::NDLB];
 #pragma unroll
@@ -166,8 +155,7 @@ __global__ __launch_bounds__(AT::NT) void attn_prefill_kernel(AttnArgs a) {
 #pragma unroll
     for (int ks = 0; ks < T::DH / 16; ++ks) {
       const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(st + koff + ks * 32);
-      const bf16x8 qf = *reinterpret_cast<const bf16x8 *>(qfrag + ks * 32);
-      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf, s, 0, 0, 0);
+      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s, 0, 0, 0);
     }
   };
   // keys after the lane's query are masked in a block that touches the diagonal
@@ -342,9 +330,6 @@ __global__ __launch_bounds__(AT::NT) void attn_prefill_kernel(AttnArgs a) {
     rotate();
   }
 
-#ifdef GTA_PROBE
-  if (tid == 0) { gta_aphase[2][wgid % 8192] = __builtin_amdgcn_s_memtime(); gta_aphase[3][wgid % 8192] = wall_clock64(); }
-#endif
   // ---- normalise, park the tile in LDS in output layout, write row-contiguous 16-byte chunks
   {
     const float inv = 1.0f / pair_sum(l_run);
