@@ -6,7 +6,8 @@ The headline metric names two things, so both are measured in every run:
     over the WHOLE gta_decode step and microseconds per generated token -- the line's `value`;
   * causal prefill of the 1B-class workload (B=4, T=4096, bf16): TFLOP/s of the whole
     gta_prefill call and fraction of the bf16 MFMA peak -- under the key "prefill".
-The batched decode workload (B=64, 8192 cached tokens) is reported under "decode_b64_8k".
+The batched decode workload (B=64, 8192 cached tokens) is reported under "decode_b64_8k" and the
+ragged packed prefill (16 sequences of 512..16384 tokens, H=4096, d_l=1024) under "varlen_prefill".
 
 A "step" is one library call (gta_decode or gta_prefill) on inputs already resident in HBM.
 `roofline` objects are for the dominant kernel of each path, timed live with HIP events around
@@ -279,7 +280,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--only", choices=["decode32k", "decode8k", "prefill"], default=None,
+    ap.add_argument("--only", choices=["decode32k", "decode8k", "prefill", "varlen"], default=None,
                     help="measure one workload only (profiling runs)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run calibration_copy_kernel once on 512 MiB (reads 512 MiB, writes 512 MiB): "
@@ -300,14 +301,16 @@ def main():
         B.gta_calibration_copy(src, dst, 512 << 20)
         torch.cuda.synchronize()
         del src, dst
-    dec = pre = dec8 = None
+    dec = pre = dec8 = var = None
     if args.only in (None, "decode32k"):
         dec = bench_decode(W.by_name("decode_b8_32k_bf16"), args.steps, args.warmup, cpu)
     if args.only in (None, "prefill"):
         pre = bench_prefill(W.by_name("prefill_1b_bf16"), args.steps, args.warmup, cpu)
     if args.only in (None, "decode8k"):
         dec8 = bench_decode(W.by_name("decode_b64_8k_bf16"), args.steps, args.warmup, False)
-    main_res = dec or pre or dec8
+    if args.only in (None, "varlen"):   # ragged packed batch, 16 sequences of 512..16384 tokens, wider model
+        var = bench_prefill(W.by_name("varlen_prefill_bf16"), min(args.steps, 10), min(args.warmup, 3), False)
+    main_res = dec or pre or dec8 or var
     line = {
         "metric": "GTA decode HBM GB/s & us/token @32K ctx; prefill bf16 TFLOP/s (% of peak)",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "higher_is_better": True, "scaling": "weak",
@@ -329,6 +332,8 @@ def main():
         line["prefill"] = pre
     if dec8 is not None and main_res is not dec8:
         line["decode_b64_8k"] = dec8
+    if var is not None and main_res is not var:
+        line["varlen_prefill"] = var
     print(json.dumps(line))
 
 

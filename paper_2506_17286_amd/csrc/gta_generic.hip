@@ -34,10 +34,8 @@ __device__ __forceinline__ float wave_sum(float v) {
 }
 
 // ------------------------------------------------------------------------------ small kernels
-__global__ void rowmap_kernel(const int32_t *cu, int batch, int64_t total, int per_seq,
-                              int32_t *seq_id, int32_t *pos) {
-  int64_t t = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
-  if (t >= total) return;
+__device__ __forceinline__ void rowmap_row(const int32_t *cu, int batch, int per_seq, int64_t t, int32_t *seq_id,
+                                           int32_t *pos) {
   if (!cu) {
     seq_id[t] = (int32_t)(t / per_seq);
     pos[t] = (int32_t)(t % per_seq);
@@ -52,15 +50,24 @@ __global__ void rowmap_kernel(const int32_t *cu, int batch, int64_t total, int p
   pos[t] = (int32_t)(t - cu[lo]);
 }
 
+__global__ void rowmap_kernel(const int32_t *cu, int batch, int64_t total, int per_seq,
+                              int32_t *seq_id, int32_t *pos) {
+  int64_t t = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+  if (t < total) rowmap_row(cu, batch, per_seq, t, seq_id, pos);
+}
+
 // (cos, sin) of pos * base^(-2j/d_h), evaluated in fp64 and rounded once to fp32 (App. B.1.1).
-__global__ void rope_table_kernel(float2 *tab, int max_pos, int half, int dh, double base) {
-  int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
-  if (i >= (int64_t)max_pos * half) return;
+__device__ __forceinline__ void rope_table_entry(float2 *tab, int half, int dh, double base, int64_t i) {
   int p = (int)(i / half), j = (int)(i % half);
   double ang = (double)p * pow(base, -2.0 * (double)j / (double)dh);
   double s, c;
   sincos(ang, &s, &c);
   tab[i] = make_float2((float)c, (float)s);
+}
+
+__global__ void rope_table_kernel(float2 *tab, int max_pos, int half, int dh, double base) {
+  int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+  if (i < (int64_t)max_pos * half) rope_table_entry(tab, half, dh, base, i);
 }
 
 // ------------------------------------------------------------------------------ generic GEMM
@@ -182,14 +189,40 @@ __global__ void finalize_prefill_kernel(Dims d, const float *praw, const int32_t
   }
 }
 
-__global__ void prefill_commit_kernel(CacheView cv, const int32_t *cu, int batch, int per_seq) {
-  int b = blockIdx.x * blockDim.x + threadIdx.x;
-  if (b >= batch) return;
+__device__ __forceinline__ void prefill_commit_seq(const CacheView &cv, const int32_t *cu, int per_seq, int b) {
   int n = cu ? cu[b + 1] - cu[b] : per_seq;
   int slot = cv.slots ? cv.slots[b] : b;
   if (slot < 0 || slot >= cv.max_batch) return;
   if (n <= cv.max_seq) cv.seq_lens[slot] = n;
   else cv.status[slot] = GTA_ERR_CACHE_FULL;
+}
+
+__global__ void prefill_commit_kernel(CacheView cv, const int32_t *cu, int batch, int per_seq) {
+  int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b < batch) prefill_commit_seq(cv, cu, per_seq, b);
+}
+
+// Everything a prefill call derives from the sequence offsets alone, in one launch: blocks
+// [0, nb_row) fill the row -> (sequence, position) map, the next nb_rope blocks the RoPE table, the
+// rest set the cached lengths (nothing below reads the lengths back during the call).
+__global__ void prefill_setup_kernel(const int32_t *cu, int batch, int64_t total, int per_seq, int32_t *seq_id,
+                                     int32_t *pos, int nb_row, float2 *tab, int max_pos, int half, int dh,
+                                     double base, int nb_rope, CacheView cv) {
+  int blk = blockIdx.x;
+  if (blk < nb_row) {
+    int64_t t = blk * (int64_t)blockDim.x + threadIdx.x;
+    if (t < total) rowmap_row(cu, batch, per_seq, t, seq_id, pos);
+    return;
+  }
+  blk -= nb_row;
+  if (blk < nb_rope) {
+    int64_t i = blk * (int64_t)blockDim.x + threadIdx.x;
+    if (i < (int64_t)max_pos * half) rope_table_entry(tab, half, dh, base, i);
+    return;
+  }
+  blk -= nb_rope;
+  int b = blk * blockDim.x + threadIdx.x;
+  if (b < batch) prefill_commit_seq(cv, cu, per_seq, b);
 }
 
 // Decode: position = tokens already cached; the new key / latent row is appended at that row.
@@ -584,6 +617,18 @@ void launch_rope_table(float2 *tab, int max_pos, int dh, double base, hipStream_
 void launch_prefill_commit(const gta_cache &cache, const int32_t *slots, const int32_t *cu, int batch,
                            int64_t total, hipStream_t st) {
   prefill_commit_kernel<<<grid1d(batch), 256, 0, st>>>(view_of(&cache, slots), cu, batch, (int)(total / batch));
+}
+
+void launch_prefill_setup(const Dims &d, const int32_t *cu, int batch, int64_t total, int max_len, int32_t *seq_id,
+                          int32_t *pos, float2 *tab, const gta_cache *cache, const int32_t *slots, hipStream_t st) {
+  if (total <= 0) return;
+  const int half = d.dh / 2;
+  const int nb_row = (int)((total + 255) / 256);
+  const int nb_rope = d.rope && max_len > 0 && half > 0 ? (int)(((int64_t)max_len * half + 255) / 256) : 0;
+  const int nb_commit = cache ? (batch + 255) / 256 : 0;
+  prefill_setup_kernel<<<nb_row + nb_rope + nb_commit, 256, 0, st>>>(
+      cu, batch, total, (int)(total / batch), seq_id, pos, nb_row, tab, max_len, half, d.dh, d.rope_base, nb_rope,
+      cache ? view_of(cache, slots) : CacheView{});
 }
 
 int generic_prefill(const Dims &d, const gta_weights &w, const void *x, const int32_t *cu, int batch,

@@ -92,6 +92,10 @@ void launch_rowmap(const int32_t *cu, int batch, int64_t total, int32_t *seq_id,
 void launch_rope_table(float2 *tab, int max_pos, int dh, double base, hipStream_t st);
 void launch_prefill_commit(const gta_cache &cache, const int32_t *slots, const int32_t *cu,
                            int batch, int64_t total, hipStream_t st);
+// row map, RoPE table (if d.rope) and cached lengths (if cache) of one prefill call in one launch
+void launch_prefill_setup(const Dims &d, const int32_t *cu, int batch, int64_t total, int max_len,
+                          int32_t *seq_id, int32_t *pos, float2 *tab, const gta_cache *cache,
+                          const int32_t *slots, hipStream_t st);
 
 // hipGetLastError after the launches of a call; with GTA_DEBUG set in the environment the HIP error
 // string goes to stderr (the only thing the library ever prints).

@@ -9,11 +9,9 @@ int tuned_prefill(const Dims &d, const gta_weights &w, const void *x, const int3
                   int max_len, const gta_cache *cache, const int32_t *slots, void *out, const PrefillWs &ws,
                   hipStream_t st) {
   const int M = (int)total;
-  launch_rowmap(cu, batch, total, ws.seq_id, ws.pos, st);
-  if (d.rope) launch_rope_table(ws.rope, max_len, d.dh, d.rope_base, st);
+  launch_prefill_setup(d, cu, batch, total, max_len, ws.seq_id, ws.pos, ws.rope, cache, slots, st);
   // Sec. 3.2 projections + App. B.1.1 RoPE + cache write, one MFMA GEMM
   launch_proj_gemm(d, w, x, M, ws, cache, slots, max_len, st);
-  if (cache) launch_prefill_commit(*cache, slots, cu, batch, total, st);
   // Sec. 3.3: one causal softmax map per group applied to the latent values
   if (attn_prefill_supported(d, max_len)) launch_attn_prefill_bf16(d, ws.q, ws.k, ws.c, cu, batch, total, max_len, ws.l, st);
   else launch_attn_prefill_rowwise(d, ws.q, ws.k, ws.c, cu, batch, total, max_len, ws.l, st);
