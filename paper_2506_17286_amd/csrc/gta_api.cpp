@@ -66,6 +66,7 @@ PrefillWs carve_prefill(const Dims &d, bool tuned, bool with_wo, int batch, int6
   w.g = cv.take<void>(n * d.wg_w * (tuned ? es : 4));
   w.l = cv.take<void>(n * (size_t)d.nq * d.dl * (tuned ? es : 4));
   w.o = cv.take<void>(with_wo ? n * d.wg_w * (tuned ? es : 4) : 0);
+  w.wpack = cv.take<void>(tuned ? proj_packed_bytes(d) : 0);
   w.bytes = cv.off;
   return w;
 }

@@ -17,13 +17,6 @@
 
 #include "gta_tuned.h"
 
-#ifdef GTA_PROBE   // phase timestamps for the standalone timing probe; never defined in the library build
-__device__ long long gta_phase[8][4096];
-#define GTA_PHASE(i) do { if (threadIdx.x == 0) gta_phase[i][blockIdx.x % 4096] = wall_clock64(); } while (0)
-#else
-#define GTA_PHASE(i)
-#endif
-
 namespace gta {
 namespace {
 
@@ -397,7 +390,6 @@ __global__ __launch_bounds__(T::NT) void proj_gemm_kernel(ProjArgs a) {
   const int m0 = mt * T::BM;
   f32x16 acc[T::TN][T::TM];
   zero_acc<T>(acc);
-  GTA_PHASE(0);
   if constexpr (T::TM == 4 && T::TN == 4) {
     const int ldb = a.width[seg];
     const unsigned boff = (unsigned)((threadIdx.x / (T::BN / 8)) * ldb + (threadIdx.x % (T::BN / 8)) * 8) * 2u;
@@ -408,7 +400,6 @@ __global__ __launch_bounds__(T::NT) void proj_gemm_kernel(ProjArgs a) {
     gemm_mainloop<T>(a.x, a.lda, a.M, m0, a.w[seg], a.width[seg], n_glob, a.K, smem, acc);
   }
 
-  GTA_PHASE(1);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wn = wave % T::WGN, wm = wave / T::WGN;
   const int nw = n_glob + wn * T::WN;            // first column of this wave inside its segment
@@ -463,7 +454,6 @@ __global__ __launch_bounds__(T::NT) void proj_gemm_kernel(ProjArgs a) {
       }
   }
   if constexpr (T::TM == 4 && T::TN == 4) {
-    GTA_PHASE(2);
     __syncthreads();                 // every wave is done with the operand stages
     tile_to_lds<T>(acc, smem);
     // cache row of every tile row (or -1), looked up once and shared through LDS
@@ -480,7 +470,6 @@ __global__ __launch_bounds__(T::NT) void proj_gemm_kernel(ProjArgs a) {
       crow_of[threadIdx.x] = cr;
     }
     __syncthreads();
-    GTA_PHASE(3);
     bf16 *dst = a.dst[seg] + n_glob;
     for_each_out_chunk(smem, [&](int r, int ch, u32x4 v) {
       const int m = m0 + r;
@@ -491,8 +480,102 @@ __global__ __launch_bounds__(T::NT) void proj_gemm_kernel(ProjArgs a) {
         if (cr >= 0) *reinterpret_cast<u32x4 *>(cache + cr * width + n_glob + ch * 8) = v;
       }
     });
-    GTA_PHASE(4);
   }
+}
+
+// ---- projection against packed weights -----------------------------------------------------------
+// The four weight matrices are first copied side by side into one [H, Wtot] matrix, so that a
+// 256-column tile may straddle Q | K | C | gate: this serves output widths that are multiples of 64
+// but not of 256 (heads of 64, a single shared key).  Columns are routed to their outputs per
+// 64-column group for RoPE (a head never straddles a group) and per 16-byte chunk for the stores.
+__global__ void pack_weights_kernel(ProjArgs a, int wtot, bf16 *dst) {
+  const int cpr = wtot / 8;   // 16-byte chunks per packed row
+  const int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+  if (i >= (int64_t)a.K * cpr) return;
+  const int k = (int)(i / cpr);
+  int col = (int)(i % cpr) * 8, seg = 0;
+  while (col >= a.width[seg]) { col -= a.width[seg]; ++seg; }
+  *reinterpret_cast<u32x4 *>(dst + i * 8) = *reinterpret_cast<const u32x4 *>(a.w[seg] + (int64_t)k * a.width[seg] + col);
+}
+
+template <class T, int DH>
+__global__ __launch_bounds__(T::NT) void proj_packed_kernel(ProjArgs a, const bf16 *wpack) {
+  static_assert(T::TM == 4 && T::TN == 4 && (DH == 64 || DH == 128), "tile");
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  const int b1 = a.width[0], b2 = b1 + a.width[1], b3 = b2 + a.width[2], wtot = b3 + a.width[3];
+  int mt, nt;
+  tile_of_block(wtot / T::BN, (a.M + T::BM - 1) / T::BM, mt, nt);
+  const int m0 = mt * T::BM, n0 = nt * T::BN;
+  f32x16 acc[T::TN][T::TM];
+  zero_acc<T>(acc);
+  {
+    const unsigned boff = (unsigned)((threadIdx.x / (T::BN / 8)) * wtot + (threadIdx.x % (T::BN / 8)) * 8) * 2u;
+    PipeStage<T> t0, t1;
+    gemm_mainloop_pipe<T>(a.x + (int64_t)m0 * a.lda, a.lda, a.M - m0, wpack + n0, boff, wtot, a.K, smem, acc, t0, t1,
+                          NoTail{});
+  }
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wn = wave % T::WGN, wm = wave / T::WGN;
+  if (a.rope) {
+    constexpr int half = DH / 2, tiles_half = DH / 64, tiles_head = DH / 32;
+#pragma unroll
+    for (int tm = 0; tm < T::TM; ++tm) {
+      const int m = m0 + wm * T::WM + tm * 32 + (lane & 31);
+      if (m >= a.M) continue;
+      const int p = a.pos[m];
+      if (p >= a.max_len) continue;
+#pragma unroll
+      for (int tn = 0; tn < T::TN; ++tn) {
+        if ((tn % tiles_head) >= tiles_half) continue;
+        const int tn_hi = tn + tiles_half;
+        if (tn_hi >= T::TN) continue;
+        if (n0 + wn * T::WN + tn * 32 >= b2) continue;   // wave-uniform: only q and k columns rotate
+#pragma unroll
+        for (int rq = 0; rq < 4; ++rq) {
+          const int j = (tn % tiles_head) * 32 + rq * 8 + (lane >> 5) * 4;
+          const float4 *tp = reinterpret_cast<const float4 *>(a.rope + (int64_t)p * half + j);
+          const float4 t0 = tp[0], t1 = tp[1];
+          const float cs[4] = {t0.x, t0.z, t1.x, t1.z}, sn[4] = {t0.y, t0.w, t1.y, t1.w};
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const float lo = acc[tn][tm][rq * 4 + i], hi = acc[tn_hi][tm][rq * 4 + i];
+            acc[tn][tm][rq * 4 + i] = lo * cs[i] - hi * sn[i];
+            acc[tn_hi][tm][rq * 4 + i] = hi * cs[i] + lo * sn[i];
+          }
+        }
+      }
+    }
+  }
+  __syncthreads();                 // every wave is done with the operand stages
+  tile_to_lds<T>(acc, smem);
+  int64_t *crow_of = reinterpret_cast<int64_t *>(smem + 256 * kOutPitch);
+  if (a.kcache) {
+    const int m = m0 + (int)threadIdx.x;
+    int64_t cr = -1;
+    if (m < a.M) {
+      const int p = a.pos[m], b = a.seq_id[m];
+      const int slot = a.slots ? a.slots[b] : b;
+      if (slot >= 0 && slot < a.max_batch && p < a.max_seq) cr = (int64_t)slot * a.max_seq + p;
+    }
+    crow_of[threadIdx.x] = cr;
+  }
+  __syncthreads();
+  // a thread stores the same 16-byte chunk column of every row: its destination is fixed
+  const int gcol = n0 + (threadIdx.x & 31) * 8;
+  const int seg = (gcol >= b1) + (gcol >= b2) + (gcol >= b3);
+  const int lcol = gcol - (seg == 0 ? 0 : seg == 1 ? b1 : seg == 2 ? b2 : b3);
+  const int width = a.width[seg];
+  bf16 *dst = a.dst[seg] + lcol;
+  bf16 *cache = !a.kcache ? nullptr : seg == 1 ? a.kcache + lcol : seg == 2 ? a.ccache + lcol : nullptr;
+  for_each_out_chunk(smem, [&](int r, int, u32x4 v) {
+    const int m = m0 + r;
+    if (m >= a.M) return;
+    *reinterpret_cast<u32x4 *>(dst + (int64_t)m * width) = v;
+    if (cache) {
+      const int64_t cr = crow_of[r];
+      if (cr >= 0) *reinterpret_cast<u32x4 *>(cache + cr * width) = v;
+    }
+  });
 }
 
 // ------------------------------------------------------------------------------ value decoder
@@ -561,7 +644,6 @@ __global__ __launch_bounds__(T::NT) void decoder_pair_kernel(DecoderArgs a) {
   const int head = nt * 2, m0 = mt * T::BM;
   f32x16 acc[T::TN][T::TM];
   zero_acc<T>(acc);
-  GTA_PHASE(0);
   const int64_t ldo = (int64_t)a.nh * a.dh;
   const int col0 = head * a.dh;
   // the gate tile (32 chunks of 16 bytes per thread: rows it*8 + tid/32, chunk tid%32) is fetched by
@@ -586,7 +668,6 @@ __global__ __launch_bounds__(T::NT) void decoder_pair_kernel(DecoderArgs a) {
     if constexpr (GATE) gemm_mainloop_pipe<T>(Ab, a.ldl, rows_valid, Bb, boff, a.dh, a.dl, smem, acc, g0, g1, gate_tail);
     else gemm_mainloop_pipe<T>(Ab, a.ldl, rows_valid, Bb, boff, a.dh, a.dl, smem, acc, g0, g1, NoTail{});
   }
-  GTA_PHASE(1);
   __syncthreads();
   if constexpr (GATE) {
 #pragma unroll
@@ -598,7 +679,6 @@ __global__ __launch_bounds__(T::NT) void decoder_pair_kernel(DecoderArgs a) {
     }
     __syncthreads();
   }
-  GTA_PHASE(2);
   // one row block (tm) at a time: all 16 gate reads of the block are issued before the first is used
 #pragma unroll
   for (int tm = 0; tm < T::TM; ++tm) {
@@ -623,11 +703,9 @@ __global__ __launch_bounds__(T::NT) void decoder_pair_kernel(DecoderArgs a) {
       }
   }
   __syncthreads();
-  GTA_PHASE(3);
   for_each_out_chunk(smem, [&](int r, int ch, u32x4 v) {
     if (m0 + r < a.M) *reinterpret_cast<u32x4 *>(a.out + (int64_t)(m0 + r) * ldo + col0 + ch * 8) = v;
   });
-  GTA_PHASE(4);
 }
 
 // ------------------------------------------------------------------------------ plain GEMM
@@ -720,6 +798,7 @@ typedef GemmTile<64, 128, 64, 1, 4> TileSkinny64;
 
 typedef GemmTile<256, 256, 64, 2, 2> TileBig;    // wave tile 128 x 128
 typedef GemmTile<256, 128, 64, 4, 1> TileHead;   // one 128-wide head per workgroup, wave tile 64(m) x 128(n)
+typedef GemmTile<256, 64, 64, 4, 1> TileHead64;  // one 64-wide head per workgroup, wave tile 64(m) x 64(n)
 
 template <class T, class K, class Args>
 void launch(K kernel, const Args &a, int ntiles, hipStream_t st) {
@@ -733,13 +812,35 @@ void launch(K kernel, const Args &a, int ntiles, hipStream_t st) {
 
 }  // namespace
 
-bool gemm_shapes_supported(const Dims &d) {
+// The pipelined 256 x 256 tile against packed weights: widths in units of a 64-column group that
+// holds whole heads, an even number (>= 4) of k-tiles.
+static bool proj_packed_ok(const Dims &d) {
+  if (d.dh != 64 && d.dh != 128) return false;
+  if (d.wq_w % d.dh || d.wk_w % d.dh || d.wc_w % 64 || d.wg_w % 64 || d.wq_w % 64 || d.wk_w % 64) return false;
+  if (d.dh == 128 && (d.wq_w % 128 || d.wk_w % 128 || d.wc_w % 128)) return false;   // head inside one wave tile
+  return d.wtot % 256 == 0 && d.H % 128 == 0 && d.H >= 256;
+}
+static bool proj_direct_ok(const Dims &d) {
   // RoPE pairing is lane-local only if a wave tile (128 columns) holds whole heads
-  if (d.dtype != GTA_BF16 || d.dh != 128) return false;
-  if (d.H % 64 || d.dl % 64 || d.wq_w % 128 || d.wk_w % 128 || d.wc_w % 128 || d.wg_w % 128) return false;
+  if (d.dh != 128) return false;
+  return !(d.H % 64 || d.dl % 64 || d.wq_w % 128 || d.wk_w % 128 || d.wc_w % 128 || d.wg_w % 128);
+}
+static bool proj_direct_big(const Dims &d) {
+  // the pipelined loop takes an even number (>= 4) of k-tiles
+  return proj_direct_ok(d) && !(d.wq_w % 256 || d.wk_w % 256 || d.wc_w % 256 || d.wg_w % 256) && d.H % 128 == 0 && d.H >= 256;
+}
+
+bool gemm_shapes_supported(const Dims &d) {
+  if (d.dtype != GTA_BF16) return false;
+  if (!proj_direct_ok(d) && !proj_packed_ok(d)) return false;
+  if (d.dl % 64) return false;
   // row offsets inside a 256-row tile are kept in 32 bits
   if (d.H > (1 << 20) || (int64_t)d.nq * d.dl > (1 << 20) || d.wg_w > (1 << 20)) return false;
   return true;
+}
+
+size_t proj_packed_bytes(const Dims &d) {
+  return d.dtype == GTA_BF16 && !proj_direct_big(d) && proj_packed_ok(d) ? (size_t)d.H * d.wtot * 2 : 0;
 }
 
 void launch_proj_gemm(const Dims &d, const gta_weights &w, const void *x, int M, const PrefillWs &ws,
@@ -749,21 +850,30 @@ void launch_proj_gemm(const Dims &d, const gta_weights &w, const void *x, int M,
   const void *wm[4] = {w.wq, w.wk, w.wc, w.wg};
   const int wd[4] = {d.wq_w, d.wk_w, d.wc_w, d.wg_w};
   void *dst[4] = {ws.q, ws.k, ws.c, ws.g};
-  bool big = true;
-  for (int i = 0; i < 4; ++i) {
-    a.w[i] = (const bf16 *)wm[i]; a.width[i] = wd[i]; a.dst[i] = (bf16 *)dst[i];
-    if (wd[i] % 256) big = false;
-  }
-  if (d.H % 128 || d.H < 256) big = false;   // the pipelined loop takes an even number (>= 4) of k-tiles
+  for (int i = 0; i < 4; ++i) { a.w[i] = (const bf16 *)wm[i]; a.width[i] = wd[i]; a.dst[i] = (bf16 *)dst[i]; }
   a.seq_id = ws.seq_id; a.pos = ws.pos;
   a.rope = d.rope ? ws.rope : nullptr; a.max_len = max_len; a.dh = d.dh;
   if (cache) {
     a.kcache = (bf16 *)cache->k; a.ccache = (bf16 *)cache->c; a.slots = slots;
     a.max_batch = cache->max_batch; a.max_seq = cache->max_seq;
   }
-  if (big) {
+  if (proj_direct_big(d)) {
     const int nt = (d.wtot / 256) * ((M + 255) / 256);
     launch<TileBig>(proj_gemm_kernel<TileBig>, a, nt, st);
+  } else if (proj_packed_ok(d)) {
+    bf16 *wpack = (bf16 *)ws.wpack;
+    const int64_t chunks = (int64_t)d.H * (d.wtot / 8);
+    pack_weights_kernel<<<(unsigned)((chunks + 255) / 256), 256, 0, st>>>(a, d.wtot, wpack);
+    const int nt = (d.wtot / 256) * ((M + 255) / 256);
+    static bool attr_set[2] = {false, false};
+    const int which = d.dh == 64 ? 0 : 1;
+    const void *fn = which == 0 ? (const void *)proj_packed_kernel<TileBig, 64> : (const void *)proj_packed_kernel<TileBig, 128>;
+    if (!attr_set[which]) {
+      (void)hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, TileBig::SMEM);
+      attr_set[which] = true;
+    }
+    if (which == 0) proj_packed_kernel<TileBig, 64><<<nt, TileBig::NT, TileBig::SMEM, st>>>(a, wpack);
+    else proj_packed_kernel<TileBig, 128><<<nt, TileBig::NT, TileBig::SMEM, st>>>(a, wpack);
   } else {
     const int nt = (d.wtot / 128) * ((M + 255) / 256);
     launch<TileHead>(proj_gemm_kernel<TileHead>, a, nt, st);
@@ -808,8 +918,11 @@ void launch_decoder_gemm(const Dims &d, const void *L, const void *wp, const voi
     else launch<TileBig>(decoder_pair_kernel<TileBig, false>, a, (d.nh / 2) * ((M + 255) / 256), st);
     return;
   }
-  const int nt = d.nh * (d.dh / 128) * ((M + 255) / 256);
-  launch<TileHead>(decoder_gemm_kernel<TileHead>, a, nt, st);
+  if (d.dh % 128 == 0) {
+    launch<TileHead>(decoder_gemm_kernel<TileHead>, a, d.nh * (d.dh / 128) * ((M + 255) / 256), st);
+  } else {   // heads of 64: one head per 64-wide tile
+    launch<TileHead64>(decoder_gemm_kernel<TileHead64>, a, d.nh * (d.dh / 64) * ((M + 255) / 256), st);
+  }
 }
 
 void launch_plain_gemm(const void *A, int64_t lda, int M, int N, int K, const void *B, void *C, hipStream_t st) {

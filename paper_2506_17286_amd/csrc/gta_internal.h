@@ -38,6 +38,7 @@ struct PrefillWs {
   void *g;                 // gate pre-activation [total, wg_w]; fp32 (generic) or dtype (tuned)
   void *l;                 // normalised group outputs [total, n_q*d_l]; fp32 (generic) or dtype
   void *o;                 // gated heads [total, wg_w] (dtype), only with W_O
+  void *wpack;             // tuned path, some shapes: [W_Q | W_K | W_C | W_G] side by side, [H, wtot]
   size_t bytes;
 };
 PrefillWs carve_prefill(const Dims &d, bool tuned, bool with_wo, int batch, int64_t total,

@@ -42,15 +42,21 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 
-struct AT {
-  static constexpr int DH = 128, DLW = 256, BK = 32, BQ = 256, NT = 512, NDLB = DLW / 32, NSTAGE = 3;
+template <int DH_, int DLW_>
+struct AttnTile {
+  static constexpr int DH = DH_, DLW = DLW_, BK = 32, BQ = 256, NT = 512, NDLB = DLW / 32, NSTAGE = 3;
   static constexpr int K_PITCH = DH * 2 + 16;      // 16 * odd: conflict-free 16-byte row reads
   static constexpr int C_PITCH = DLW * 2 + 64;     // == 64 mod 256: conflict-free transpose reads
   static constexpr int K_BYTES = BK * K_PITCH, C_BYTES = BK * C_PITCH, STAGE = K_BYTES + C_BYTES;
   static constexpr int OUT_PITCH = DLW * 2 + 16;
   static constexpr int SMEM = BQ * OUT_PITCH > NSTAGE * STAGE ? BQ * OUT_PITCH : NSTAGE * STAGE;
-  static constexpr int K_LOADS = BK * (DH / 8) / NT, C_LOADS = BK * (DLW / 8) / NT;   // 1, 2
-  static_assert(SMEM >= BQ * OUT_PITCH && SMEM <= 160 * 1024, "LDS budget");
+  // 16-byte chunks per tile row, tile rows one pass of the 512 threads covers, passes per tile
+  static constexpr int K_CPR = DH / 8, C_CPR = DLW / 8, K_CHUNKS = BK * K_CPR;
+  static constexpr int C_RPP = NT / C_CPR, C_LOADS = BK / C_RPP;
+  // the hand-scheduled main loop below is written for this shape; others take the plain loop
+  static constexpr bool PIPELINED = DH == 128 && DLW == 256;
+  static_assert(DH % 16 == 0 && DLW % 32 == 0 && K_CHUNKS <= NT && BK % C_RPP == 0 && C_LOADS >= 1, "tile");
+  static_assert(SMEM <= 160 * 1024, "LDS budget");
 };
 
 struct AttnArgs {
@@ -73,8 +79,8 @@ __device__ __forceinline__ float pair_sum(float v) {
   return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
-__global__ __launch_bounds__(AT::NT) void attn_prefill_kernel(AttnArgs a) {
-  typedef AT T;
+template <class T>
+__global__ __launch_bounds__(T::NT) void attn_prefill_kernel(AttnArgs a) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const int tid = threadIdx.x, lane = tid & 63, h = lane >> 5, ln = lane & 31;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: branches on it are scalar
@@ -122,28 +128,26 @@ __global__ __launch_bounds__(AT::NT) void attn_prefill_kernel(AttnArgs a) {
 
   // cooperative tile staging: global -> registers -> LDS; rows past the sequence re-read its last row
   // (such keys are in the future of every valid query and are masked)
-  u32x4 rk[T::K_LOADS], rc[T::C_LOADS];
-  const int k_row = tid >> 4, k_ch = tid & 15, c_row = tid >> 5, c_ch = tid & 31;
+  u32x4 rk, rc[T::C_LOADS];
+  const int k_row = tid / T::K_CPR, k_ch = tid % T::K_CPR, c_row = tid / T::C_CPR, c_ch = tid % T::C_CPR;
+  const bool k_loader = tid < T::K_CHUNKS;   // a narrow key tile has fewer chunks than threads
   auto gload = [&](int t) {
     const int j0 = t * T::BK;
-#pragma unroll
-    for (int i = 0; i < T::K_LOADS; ++i) {
-      const unsigned r = min(j0 + k_row + i * 32, Tb - 1);   // K_LOADS == 1
-      rk[i] = *reinterpret_cast<const u32x4 *>(Kb + (r * wk2 + k_ch * 16));
+    if (k_loader) {
+      const unsigned r = min(j0 + k_row, Tb - 1);
+      rk = *reinterpret_cast<const u32x4 *>(Kb + (r * wk2 + k_ch * 16));
     }
 #pragma unroll
     for (int i = 0; i < T::C_LOADS; ++i) {
-      const unsigned r = min(j0 + c_row + i * 16, Tb - 1);
+      const unsigned r = min(j0 + c_row + i * T::C_RPP, Tb - 1);
       rc[i] = *reinterpret_cast<const u32x4 *>(Cb + (r * wc2 + c_ch * 16));
     }
   };
   auto sstore = [&](char *st) {
-#pragma unroll
-    for (int i = 0; i < T::K_LOADS; ++i)
-      *reinterpret_cast<u32x4 *>(st + (k_row + i * 32) * T::K_PITCH + k_ch * 16) = rk[i];
+    if (k_loader) *reinterpret_cast<u32x4 *>(st + k_row * T::K_PITCH + k_ch * 16) = rk;
 #pragma unroll
     for (int i = 0; i < T::C_LOADS; ++i)
-      *reinterpret_cast<u32x4 *>(st + T::K_BYTES + (c_row + i * 16) * T::C_PITCH + c_ch * 16) = rc[i];
+      *reinterpret_cast<u32x4 *>(st + T::K_BYTES + (c_row + i * T::C_RPP) * T::C_PITCH + c_ch * 16) = rc[i];
   };
   const int koff = ln * T::K_PITCH + h * 16;
   const int coff = T::K_BYTES + (4 * h + ((lane & 15) >> 2)) * T::C_PITCH + (((lane >> 4) & 1) * 16 + (lane & 3) * 4) * 2;
@@ -246,8 +250,9 @@ __global__ __launch_bounds__(AT::NT) void attn_prefill_kernel(AttnArgs a) {
     }
   };
   // main part: blocks t and t+1 both lie entirely below this wave's diagonal
-  const int t_main = min(nb_w, qw0 >> 5) - 1;   // iterations 0 .. t_main-1
   int t = 0;
+  if constexpr (T::PIPELINED) {
+  const int t_main = min(nb_w, qw0 >> 5) - 1;   // iterations 0 .. t_main-1
 #pragma unroll 1
   for (; t < t_main; ++t) {
     sstore(smem + fre);
@@ -306,6 +311,7 @@ __global__ __launch_bounds__(AT::NT) void attn_prefill_kernel(AttnArgs a) {
     __syncthreads();
     rotate();
   }
+  }
   // the blocks around the diagonal, then idle iterations that only keep staging for the other waves
 #pragma unroll 1
   for (; t < ntiles; ++t) {
@@ -346,14 +352,31 @@ __global__ __launch_bounds__(AT::NT) void attn_prefill_kernel(AttnArgs a) {
   }
   __syncthreads();
   bf16 *Lb = a.L + (start + q0) * (int64_t)(a.nq * a.dl) + g * a.dl + dlc * T::DLW;
-  const int r0 = tid >> 5, ch = tid & 31;
+  constexpr int CPR = T::DLW / 8, RPP = T::NT / CPR;   // 16-byte chunks per output row, rows per pass
+  const int r0 = tid / CPR, ch = tid % CPR;
 #pragma unroll 4
-  for (int it = 0; it < 16; ++it) {
-    const int r = it * 16 + r0;
+  for (int it = 0; it < T::BQ / RPP; ++it) {
+    const int r = it * RPP + r0;
     if (q0 + r < Tb)
       *reinterpret_cast<u32x4 *>(Lb + (int64_t)r * (a.nq * a.dl) + ch * 8) =
           *reinterpret_cast<const u32x4 *>(smem + r * T::OUT_PITCH + ch * 16);
   }
+}
+
+typedef AttnTile<128, 256> AttnWide;     // d_h = 128, latent width a multiple of 256
+typedef AttnTile<64, 128> AttnNarrow;    // d_h = 64, latent width a multiple of 128
+
+template <class T>
+void launch_attn(const AttnArgs &a0, const Dims &d, int batch, int max_len, hipStream_t st) {
+  AttnArgs a = a0;
+  a.n_qtiles = (max_len + T::BQ - 1) / T::BQ;
+  a.ndlc = d.dl / T::DLW;
+  static bool attr_set = false;
+  if (!attr_set) {
+    (void)hipFuncSetAttribute((const void *)attn_prefill_kernel<T>, hipFuncAttributeMaxDynamicSharedMemorySize, T::SMEM);
+    attr_set = true;
+  }
+  attn_prefill_kernel<T><<<a.n_qtiles * a.ndlc * d.nq * batch, T::NT, T::SMEM, st>>>(a);
 }
 
 }  // namespace
@@ -361,7 +384,8 @@ __global__ __launch_bounds__(AT::NT) void attn_prefill_kernel(AttnArgs a) {
 bool attn_prefill_supported(const Dims &d, int max_len) {
   // byte offsets inside one sequence's K / C rows are kept in 32 bits
   if ((int64_t)max_len * d.wc_w * 2 >= ((int64_t)1 << 31) || (int64_t)max_len * d.wk_w * 2 >= ((int64_t)1 << 31)) return false;
-  return d.dtype == GTA_BF16 && d.dh == 128 && d.dl % 256 == 0 && d.wk_w % 8 == 0 && d.wc_w % 8 == 0;
+  if (d.dtype != GTA_BF16 || d.wq_w % 8 || d.wk_w % 8 || d.wc_w % 8) return false;
+  return (d.dh == 128 && d.dl % 256 == 0) || (d.dh == 64 && d.dl % 128 == 0);
 }
 
 void launch_attn_prefill_bf16(const Dims &d, const void *q, const void *k, const void *c, const int32_t *cu,
@@ -370,15 +394,10 @@ void launch_attn_prefill_bf16(const Dims &d, const void *q, const void *k, const
   a.q = (const bf16 *)q; a.k = (const bf16 *)k; a.c = (const bf16 *)c; a.L = (bf16 *)L;
   a.cu = cu; a.per_seq = (int)(total / batch);
   a.nq = d.nq; a.qpk = d.qpk; a.qpc = d.qpc; a.wq_w = d.wq_w; a.wk_w = d.wk_w; a.wc_w = d.wc_w; a.dl = d.dl;
-  a.n_qtiles = (max_len + AT::BQ - 1) / AT::BQ;
   a.scale_log2e = d.scale * 1.4426950408889634f;
-  static bool attr_set = false;
-  if (!attr_set) {
-    (void)hipFuncSetAttribute((const void *)attn_prefill_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, AT::SMEM);
-    attr_set = true;
-  }
-  a.ndlc = d.dl / AT::DLW; a.batch = batch;
-  attn_prefill_kernel<<<a.n_qtiles * a.ndlc * d.nq * batch, AT::NT, AT::SMEM, st>>>(a);
+  a.batch = batch;
+  if (d.dh == 128) launch_attn<AttnWide>(a, d, batch, max_len, st);
+  else launch_attn<AttnNarrow>(a, d, batch, max_len, st);
 }
 
 }  // namespace gta

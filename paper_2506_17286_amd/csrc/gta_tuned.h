@@ -21,6 +21,7 @@ void tuned_decode_combine(const Dims &d, const float *part, const int32_t *oldle
 
 // bf16 MFMA GEMMs (gta_gemm_bf16.hip)
 bool gemm_shapes_supported(const Dims &d);
+size_t proj_packed_bytes(const Dims &d);   // workspace for the packed [H, Wtot] weights, 0 if not used
 void launch_proj_gemm(const Dims &d, const gta_weights &w, const void *x, int M, const PrefillWs &ws,
                       const gta_cache *cache, const int32_t *slots, int max_len, hipStream_t st);
 void launch_decoder_gemm(const Dims &d, const void *L, const void *wp, const void *g, void *out, int M,

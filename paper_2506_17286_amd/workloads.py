@@ -58,8 +58,18 @@ WORKLOADS: List[Workload] = [
 ]
 
 
+# One attention layer of the paper's 1B-class models (Appendix, model hyper-parameter table): hidden
+# size 1280, 20 heads of 64, GTA-1B with 5 map groups, one shared key and one 128-wide latent value;
+# batch sizes and lengths from the paper's efficiency runs (prefill 32 x up to 2048 tokens, decode at
+# batch 64).  Seeds continue after the benchmark table.
+PAPER_WORKLOADS: List[Workload] = [
+    Workload("gta1b_prefill_b32_t2048", "prefill", 32, 2048, 1280, 20, 5, 1, 1, 64, 128, "bf16", True, seed=1100),
+    Workload("gta1b_decode_b64_t2048", "decode", 64, 2048, 1280, 20, 5, 1, 1, 64, 128, "bf16", True, seed=1101),
+]
+
+
 def by_name(name: str) -> Workload:
-    for w in WORKLOADS:
+    for w in WORKLOADS + PAPER_WORKLOADS:
         if w.name == name:
             return w
     raise KeyError(name)

@@ -126,11 +126,19 @@ def test_tuned_decode_ragged_contexts(shape):
         assert np.array_equal(cache.seq_lens.cpu().numpy(), sl)
 
 
-@pytest.mark.parametrize("shape,with_wo", [("1b", False), ("1b", True), ("wide", False)])
+@pytest.mark.parametrize("shape,with_wo", [("1b", False), ("1b", True), ("wide", False), ("paper", False),
+                                           ("paper", True), ("packed128", False)])
 def test_tuned_prefill_ragged_small(shape, with_wo):
-    """The MFMA prefill path (1B and wide shapes) on short ragged sequences spanning several tiles
-    and tails, every output element and every cached row against the oracle."""
-    base = W.WORKLOADS[1] if shape == "1b" else W.WORKLOADS[4]
+    """The MFMA prefill path (1B and wide shapes, the paper's own layer shape with heads of 64 and one
+    shared key, and a shape with heads of 128 whose tiles straddle the Q | K | C | gate boundaries) on
+    short ragged sequences spanning several tiles and tails, every output element and every cached row
+    against the oracle."""
+    if shape == "paper":
+        base = W.PAPER_WORKLOADS[0]
+    elif shape == "packed128":
+        base = W.scaled(W.WORKLOADS[1], d_model=512, n_heads=4, n_qgroups=2, n_kgroups=1, n_cgroups=1, latent_dim=128)
+    else:
+        base = W.WORKLOADS[1] if shape == "1b" else W.WORKLOADS[4]
     lens = [1, 37, 256, 300, 129, 64]
     wl = W.scaled(base, batch=len(lens), seqlen=max(lens), min_seqlen=None)
     assert B.gta_uses_tuned_kernels(B.config_of(wl), B.GTA_MODE_PREFILL) == 1
