@@ -390,6 +390,234 @@ __global__ __launch_bounds__(256, S::OCC) void decode_attn_kernel(DecAttnArgs a,
   }
 }
 
+// ---- narrow rows: one shared key of 64 and one latent of 128 (the paper's own model shapes) --------
+// A cache row is only 128 + 256 bytes, so one 1 KiB wave load covers 8 key rows (8 lanes each) or 4
+// latent rows (16 lanes each).  A wave takes 8 rows per step: one key load and two latent loads.
+// Scores are formed in the key layout (lane l: row l/8), the latent accumulators live in the latent
+// layout (lane l: rows l/16 and 4 + l/16 of the step), so a wave runs four independent online-softmax
+// streams (rows c and c+4 of every step, c = 0..3): the two key-layout lane groups of a stream are 32
+// lanes apart and agree on its statistics with one exchange, and the latent-layout lanes of stream c
+// fetch its two probabilities and its rescale factor from lane 8c.  Streams, waves and splits are
+// merged with the usual log-sum-exp weights.  Same three call modes as the kernel above.
+template <int NQ>
+__global__ __launch_bounds__(256) void decode_narrow_kernel(DecAttnArgs a, RopeFreq rf) {
+  constexpr int DH = 64, DL = 128, WQ = NQ * DH, WK = DH, WC = DL, half = DH / 2, R = 8;
+  constexpr int KROW = WK / 8, CROW = WC / 8;   // 16-byte words per cache row
+  static_assert(WQ / 2 <= 256 && WC <= 256, "prologue mapping");
+  __shared__ float sm[kWaves][NQ], sl[kWaves][NQ];
+  __shared__ float lacc[NQ * DL];
+  __shared__ float qs[WQ];                                       // rotated queries * scale * log2(e)
+  __shared__ __attribute__((aligned(16))) bf16 newrow[WK + WC];  // fused step: the new token's k | c row
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int s = blockIdx.x, b = blockIdx.y, splits = a.splits;
+  float *pa = a.pacc + (int64_t)(b * splits + s) * NQ * DL;
+  float *pm = a.pml + (int64_t)(b * splits + s) * NQ * 2;
+  const int slot = a.slots ? a.slots[b] : b;
+  const bool slot_ok = slot >= 0 && slot < a.max_batch;
+  int old;   // index of the newest row that takes part
+  if (a.oldlen_in) old = a.oldlen_in[b];
+  else if (a.praw) { const int p = slot_ok ? a.seq_lens[slot] : -1; old = (p >= 0 && p < a.max_seq) ? p : -1; }
+  else old = (slot_ok ? min(a.seq_lens[slot], a.max_seq) : 0) - 1;
+  if (a.oldlen_out && s == 0 && tid == 0) a.oldlen_out[b] = old;
+  if (old < 0 && (a.praw || a.oldlen_in)) {   // slot full: the tail kernel zero-fills this sequence
+    if (tid < NQ) { pm[2 * tid] = -INFINITY; pm[2 * tid + 1] = 0.f; }
+    return;
+  }
+  const int n = old + 1;
+  const int64_t units = (n + R - 1) / R;
+  const int j0 = min(n, (int)(units * s / splits) * R);
+  int j1 = s + 1 == splits ? n : min(n, (int)(units * (s + 1) / splits) * R);
+  const bool has_new = a.praw != nullptr && j0 < j1 && j1 == n;
+  if (has_new) j1 -= 1;
+  const u32x4 *Kp = reinterpret_cast<const u32x4 *>(a.kc + (int64_t)slot * a.max_seq * WK);
+  const u32x4 *Cp = reinterpret_cast<const u32x4 *>(a.cc + (int64_t)slot * a.max_seq * WC);
+
+  float m[NQ], l[NQ], acc[NQ][8];
+#pragma unroll
+  for (int g = 0; g < NQ; ++g) {
+    m[g] = -INFINITY; l[g] = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[g][e] = 0.f;
+  }
+  const int nblk = (j1 - j0 + R - 1) / R;   // j1 - j0 may be 0 (only the new row)
+  struct Blk { u32x4 k, c0, c1; };
+  Blk bA, bB;
+  auto load = [&](Blk &bk, int blk) {   // rows past the slice re-read its last row; weight 0
+    const int jb = j0 + blk * R;
+    bk.k = __builtin_nontemporal_load(Kp + (int64_t)min(jb + (lane >> 3), j1 - 1) * KROW + (lane & 7));
+    bk.c0 = __builtin_nontemporal_load(Cp + (int64_t)min(jb + (lane >> 4), j1 - 1) * CROW + (lane & 15));
+    bk.c1 = __builtin_nontemporal_load(Cp + (int64_t)min(jb + 4 + (lane >> 4), j1 - 1) * CROW + (lane & 15));
+  };
+
+  // ---- queries (and the new row) into LDS; the first cache blocks are requested right behind the
+  // partial sums so that the stream is in flight while the queries are reduced and rotated
+  const int64_t pstride = (int64_t)a.batch * a.wtot;
+  const float *pb = a.praw ? a.praw + (int64_t)b * a.wtot : nullptr;
+  auto col_sum = [&](int c) {
+    float pv[16];
+#pragma unroll
+    for (int k = 0; k < 16; ++k) pv[k] = k < a.nsum ? pb[k * pstride + c] : 0.f;
+    float v = 0.f;
+#pragma unroll
+    for (int k = 0; k < 16; ++k) v += pv[k];
+    return v;
+  };
+  auto rotate = [&](float &lo, float &hi, int j) {
+    if (!a.rope) return;
+    float sn, cs;
+    rope_sincos(old, rf.f[j], sn, cs);
+    const float l2 = lo * cs - hi * sn, h2 = hi * cs + lo * sn;
+    lo = l2; hi = h2;
+  };
+  const bool q_thread = tid < WQ / 2;
+  const int qc0 = (tid / half) * DH + tid % half;   // rotation pair (qc0, qc0 + d_h/2)
+  float q_lo = 0.f, q_hi = 0.f;
+  if (q_thread) {
+    if (a.praw) { q_lo = col_sum(qc0); q_hi = col_sum(qc0 + half); }
+    else { q_lo = a.q_direct[(int64_t)b * WQ + qc0]; q_hi = a.q_direct[(int64_t)b * WQ + qc0 + half]; }
+  }
+  __builtin_amdgcn_sched_barrier(0);
+  if (wave < nblk) load(bA, wave);
+  if (wave + kWaves < nblk) load(bB, wave + kWaves);
+  __builtin_amdgcn_sched_barrier(0);
+  if (q_thread) {
+    if (a.praw) rotate(q_lo, q_hi, tid % half);
+    qs[qc0] = q_lo * a.scale_log2e;
+    qs[qc0 + half] = q_hi * a.scale_log2e;
+  }
+  if (has_new) {   // the new token's key row (rotated) and latent row: LDS for this workgroup, cache for the rest
+    bf16 *krow = a.kc + ((int64_t)slot * a.max_seq + old) * WK, *crow = a.cc + ((int64_t)slot * a.max_seq + old) * WC;
+    if (tid < half) {
+      float k_lo = col_sum(WQ + tid), k_hi = col_sum(WQ + tid + half);
+      rotate(k_lo, k_hi, tid);
+      const bf16 rl = (bf16)k_lo, rh = (bf16)k_hi;
+      newrow[tid] = rl; newrow[tid + half] = rh;
+      krow[tid] = rl; krow[tid + half] = rh;
+    }
+    if (tid >= 64 && tid < 64 + WC) {
+      const int c = tid - 64;
+      const bf16 r = (bf16)col_sum(WQ + WK + c);
+      newrow[WK + c] = r;
+      crow[c] = r;
+    }
+  }
+  __syncthreads();
+
+  float qf[NQ][8];   // this lane's eighth of every query
+#pragma unroll
+  for (int g = 0; g < NQ; ++g)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) qf[g][e] = qs[g * DH + (lane & 7) * 8 + e];
+  const int src = (lane >> 4) << 3;   // key-layout lane that holds this latent-layout lane's stream
+  auto compute = [&](const Blk &bk, int nv) {
+    float kf[8], p[NQ], p2[NQ], corr[NQ];
+    unpack8(bk.k, kf);
+    const bool valid = (lane >> 3) < nv;
+#pragma unroll
+    for (int g = 0; g < NQ; ++g) {
+      float sc = 0.f;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) sc = fmaf(qf[g][e], kf[e], sc);
+      sc = group_sum<8>(sc);
+      sc = valid ? sc : -INFINITY;
+      const float sc2 = __shfl_xor(sc, 32, 64);              // the stream's other row of this step
+      const float mn = fmaxf(m[g], fmaxf(sc, sc2));
+      const float ref = mn > -INFINITY ? mn : 0.f;            // a stream that has seen no row yet
+      corr[g] = fast_exp2(m[g] - ref);
+      p[g] = fast_exp2(sc - ref);
+      p2[g] = fast_exp2(sc2 - ref);
+      l[g] = fmaf(l[g], corr[g], p[g] + p2[g]);
+      m[g] = mn;
+    }
+    float c0[8], c1[8];
+    unpack8(bk.c0, c0);
+    unpack8(bk.c1, c1);
+#pragma unroll
+    for (int g = 0; g < NQ; ++g) {
+      // lane src sits in the key layout on row src/8 = lane/16 (< 4): its p is the first latent load's
+      // probability, its p2 the second's
+      const float pA = __shfl(p[g], src, 64), pB = __shfl(p2[g], src, 64), cr = __shfl(corr[g], src, 64);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[g][e] = fmaf(pB, c1[e], fmaf(pA, c0[e], acc[g][e] * cr));
+    }
+  };
+  auto nvalid = [&](int blk) { return min(R, j1 - (j0 + blk * R)); };
+  int blk = wave;
+  while (blk < nblk) {
+    if (blk != wave && blk + kWaves < nblk) load(bB, blk + kWaves);   // the first pair is already in flight
+    compute(bA, nvalid(blk));
+    blk += kWaves;
+    if (blk >= nblk) break;
+    if (blk + kWaves < nblk) load(bA, blk + kWaves);
+    compute(bB, nvalid(blk));
+    blk += kWaves;
+  }
+  if (has_new && wave == 0) {   // the new token's own row, from LDS: one more step with a single valid row
+    const u32x4 *nr = reinterpret_cast<const u32x4 *>(newrow);
+    bA.k = nr[lane & 7];
+    bA.c0 = nr[KROW + (lane & 15)];
+    bA.c1 = bA.c0;
+    compute(bA, 1);
+  }
+
+  // ---- merge the four streams of the wave, then the four waves (fixed order), write the partial
+  float mw[NQ], lw[NQ];
+#pragma unroll
+  for (int g = 0; g < NQ; ++g) {
+    float mx = fmaxf(m[g], __shfl_xor(m[g], 8, 64));
+    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+    const float ref = mx > -INFINITY ? mx : 0.f;
+    float lv = l[g] * fast_exp2(m[g] - ref);     // 0 for a stream without rows
+    lv += __shfl_xor(lv, 8, 64);
+    lv += __shfl_xor(lv, 16, 64);                // lanes l, l^8, l^16, l^24: one lane group of each stream
+    const float ms = __shfl(m[g], src, 64);      // this latent-layout lane's stream
+    const float sc = fast_exp2(ms - ref);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      float v = acc[g][e] * sc;
+      v += __shfl_xor(v, 16, 64);
+      v += __shfl_xor(v, 32, 64);
+      acc[g][e] = v;
+    }
+    mw[g] = mx; lw[g] = lv;
+  }
+  if (lane == 0) {
+#pragma unroll
+    for (int g = 0; g < NQ; ++g) { sm[wave][g] = mw[g]; sl[wave][g] = lw[g]; }
+  }
+  __syncthreads();
+  for (int w = 0; w < kWaves; ++w) {
+    if (wave == w && lane < 16) {
+#pragma unroll
+      for (int g = 0; g < NQ; ++g) {
+        float mx = sm[0][g];
+#pragma unroll
+        for (int x = 1; x < kWaves; ++x) mx = fmaxf(mx, sm[x][g]);
+        const float ws = mw[g] > -INFINITY ? fast_exp2(mw[g] - mx) : 0.f;
+        float *dst = lacc + g * DL + lane * 8;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const float val = acc[g][e] * ws;
+          dst[e] = (w == 0) ? val : dst[e] + val;
+        }
+      }
+    }
+    __syncthreads();
+  }
+  for (int i = tid; i < NQ * DL; i += 256) pa[i] = lacc[i];
+  if (tid < NQ) {
+    const int g = tid;
+    float mx = sm[0][g];
+    for (int w = 1; w < kWaves; ++w) mx = fmaxf(mx, sm[w][g]);
+    float ls = 0.f;
+    for (int w = 0; w < kWaves; ++w)
+      if (sm[w][g] > -INFINITY) ls += sl[w][g] * fast_exp2(sm[w][g] - mx);
+    pm[2 * g] = mx;
+    pm[2 * g + 1] = ls;
+  }
+}
+
 // Combine of the splits of one (sequence, map group): weights exp2(m_s - max) / sum_s exp2(m_s - max) l_s.
 // grid (d_l / 256, n_q, batch); a full slot (oldlen < 0) gives a zero row.
 __global__ __launch_bounds__(256) void decode_combine_kernel(Dims d, const float *__restrict__ pacc,
@@ -761,9 +989,14 @@ bool matches(const Dims &d) {
 
 }  // namespace
 
+// one shared key of 64, one latent of 128, 3 / 5 / 6 maps (the paper's 160M, 500M and 1B GTA models)
+static bool narrow_shape(const Dims &d) {
+  return d.dh == 64 && d.nk == 1 && d.nc == 1 && d.dl == 128 && (d.nq == 3 || d.nq == 5 || d.nq == 6);
+}
+
 bool tuned_decode_supported(const Dims &d) {
   if (d.dtype != GTA_BF16) return false;
-  return matches<Shape1B>(d) || matches<ShapeWide>(d);
+  return matches<Shape1B>(d) || matches<ShapeWide>(d) || narrow_shape(d);
 }
 
 static DecAttnArgs attn_args(const Dims &d, const gta_cache &cache, const int32_t *slots, int batch, int splits,
@@ -779,7 +1012,10 @@ static DecAttnArgs attn_args(const Dims &d, const gta_cache &cache, const int32_
 
 static void launch_attn_any(const Dims &d, const DecAttnArgs &a, const RopeFreq &rf, int batch, hipStream_t st) {
   if (matches<Shape1B>(d)) launch_attn<Shape1B>(d, a, rf, batch, st);
-  else launch_attn<ShapeWide>(d, a, rf, batch, st);
+  else if (matches<ShapeWide>(d)) launch_attn<ShapeWide>(d, a, rf, batch, st);
+  else if (d.nq == 3) decode_narrow_kernel<3><<<dim3(a.splits, batch), 256, 0, st>>>(a, rf);
+  else if (d.nq == 5) decode_narrow_kernel<5><<<dim3(a.splits, batch), 256, 0, st>>>(a, rf);
+  else decode_narrow_kernel<6><<<dim3(a.splits, batch), 256, 0, st>>>(a, rf);
 }
 
 // q already rotated.  oldlen_in NULL: attend over the rows the caches hold now (stage call); otherwise

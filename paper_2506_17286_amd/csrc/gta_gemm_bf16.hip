@@ -516,20 +516,20 @@ __global__ __launch_bounds__(T::NT) void proj_packed_kernel(ProjArgs a, const bf
   }
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wn = wave % T::WGN, wm = wave / T::WGN;
-  if (a.rope) {
+  if (a.rope && n0 < b2) {   // the tile holds q or k columns
     constexpr int half = DH / 2, tiles_half = DH / 64, tiles_head = DH / 32;
 #pragma unroll
     for (int tm = 0; tm < T::TM; ++tm) {
       const int m = m0 + wm * T::WM + tm * 32 + (lane & 31);
-      if (m >= a.M) continue;
-      const int p = a.pos[m];
-      if (p >= a.max_len) continue;
+      const int p = min(a.pos[min(m, a.M - 1)], a.max_len - 1);
 #pragma unroll
       for (int tn = 0; tn < T::TN; ++tn) {
         if ((tn % tiles_head) >= tiles_half) continue;
         const int tn_hi = tn + tiles_half;
         if (tn_hi >= T::TN) continue;
-        if (n0 + wn * T::WN + tn * 32 >= b2) continue;   // wave-uniform: only q and k columns rotate
+        // latent and gate columns of a straddling tile take the identity rotation (no branch: the
+        // accumulators stay where they are)
+        const bool rot = n0 + wn * T::WN + tn * 32 < b2;
 #pragma unroll
         for (int rq = 0; rq < 4; ++rq) {
           const int j = (tn % tiles_head) * 32 + rq * 8 + (lane >> 5) * 4;
@@ -538,9 +538,10 @@ __global__ __launch_bounds__(T::NT) void proj_packed_kernel(ProjArgs a, const bf
           const float cs[4] = {t0.x, t0.z, t1.x, t1.z}, sn[4] = {t0.y, t0.w, t1.y, t1.w};
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
+            const float c = rot ? cs[i] : 1.f, sv = rot ? sn[i] : 0.f;
             const float lo = acc[tn][tm][rq * 4 + i], hi = acc[tn_hi][tm][rq * 4 + i];
-            acc[tn][tm][rq * 4 + i] = lo * cs[i] - hi * sn[i];
-            acc[tn_hi][tm][rq * 4 + i] = hi * cs[i] + lo * sn[i];
+            acc[tn][tm][rq * 4 + i] = lo * c - hi * sv;
+            acc[tn_hi][tm][rq * 4 + i] = hi * c + lo * sv;
           }
         }
       }
@@ -708,6 +709,68 @@ __global__ __launch_bounds__(T::NT) void decoder_pair_kernel(DecoderArgs a) {
   });
 }
 
+// All 256 / d_h heads of one 256-wide tile share the row operand L_g (they lie in one map group);
+// short contraction (d_l of 64 .. 192, or any multiple of 64): plain main loop.  The gate tile is
+// fetched with coalesced 16-byte loads before the main loop starts and applied as above.
+template <class T, bool GATE>
+__global__ __launch_bounds__(T::NT) void decoder_multi_kernel(DecoderArgs a) {
+  static_assert(T::BM == 256 && T::BN == 256 && T::NT == 256, "tile");
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  const int hpt = T::BN / a.dh;   // heads per tile
+  int mt, nt;
+  tile_of_block(a.nh / hpt, (a.M + T::BM - 1) / T::BM, mt, nt);
+  const int head = nt * hpt, m0 = mt * T::BM;
+  f32x16 acc[T::TN][T::TM];
+  zero_acc<T>(acc);
+  const int64_t ldo = (int64_t)a.nh * a.dh;
+  const int col0 = head * a.dh;
+  const int r0 = threadIdx.x >> 5, ch = threadIdx.x & 31;
+  u32x4 gt[32];
+  if constexpr (GATE) {
+    const bf16 *gp = a.g + col0 + ch * 8;
+#pragma unroll
+    for (int it = 0; it < 32; ++it)
+      gt[it] = *reinterpret_cast<const u32x4 *>(gp + (int64_t)min(m0 + it * 8 + r0, a.M - 1) * ldo);
+  }
+  {
+    // column chunk -> head of the tile: the loop adds (chunk column) to the pointer it is given
+    const int col = (threadIdx.x % (T::BN / 8)) * 8;
+    const bf16 *Bt = a.wp + (int64_t)head * a.dl * a.dh + (int64_t)(col / a.dh) * a.dl * a.dh + (col % a.dh) - col;
+    gemm_mainloop<T>(a.L + (head / a.hpq) * a.dl, a.ldl, a.M, m0, Bt, a.dh, 0, a.dl, smem, acc);
+  }
+  if constexpr (GATE) {
+#pragma unroll
+    for (int it = 0; it < 32; ++it) *reinterpret_cast<u32x4 *>(smem + (it * 8 + r0) * kOutPitch + ch * 16) = gt[it];
+    __syncthreads();
+  }
+#pragma unroll
+  for (int tm = 0; tm < T::TM; ++tm) {
+    bf16x4 gz[T::TN][4];
+    if constexpr (GATE) {
+#pragma unroll
+      for (int tn = 0; tn < T::TN; ++tn)
+#pragma unroll
+        for (int rq = 0; rq < 4; ++rq) gz[tn][rq] = *reinterpret_cast<const bf16x4 *>(smem + out_lds_offset<T>(tm, tn, rq));
+    }
+#pragma unroll
+    for (int tn = 0; tn < T::TN; ++tn)
+#pragma unroll
+      for (int rq = 0; rq < 4; ++rq) {
+        float v[4] = {acc[tn][tm][rq * 4], acc[tn][tm][rq * 4 + 1], acc[tn][tm][rq * 4 + 2], acc[tn][tm][rq * 4 + 3]};
+        if constexpr (GATE) {
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+            v[i] *= __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * (float)gz[tn][rq][i]));
+        }
+        *reinterpret_cast<bf16x4 *>(smem + out_lds_offset<T>(tm, tn, rq)) = pack4(v[0], v[1], v[2], v[3]);
+      }
+  }
+  __syncthreads();
+  for_each_out_chunk(smem, [&](int r, int ch, u32x4 v) {
+    if (m0 + r < a.M) *reinterpret_cast<u32x4 *>(a.out + (int64_t)(m0 + r) * ldo + col0 + ch * 8) = v;
+  });
+}
+
 // ------------------------------------------------------------------------------ plain GEMM
 struct PlainArgs { const bf16 *A; int64_t lda; int M, N, K; const bf16 *B; bf16 *C; };
 
@@ -795,17 +858,28 @@ __global__ __launch_bounds__(T::NT) void skinny_proj_kernel(SkinnyArgs a) {
 
 typedef GemmTile<32, 128, 64, 1, 4> TileSkinny32;
 typedef GemmTile<64, 128, 64, 1, 4> TileSkinny64;
+typedef GemmTile<32, 64, 64, 1, 2> TileSkinny32N64;   // 64-wide tiles for widths that are not multiples of 128
+typedef GemmTile<64, 64, 64, 2, 2> TileSkinny64N64;
 
 typedef GemmTile<256, 256, 64, 2, 2> TileBig;    // wave tile 128 x 128
 typedef GemmTile<256, 128, 64, 4, 1> TileHead;   // one 128-wide head per workgroup, wave tile 64(m) x 128(n)
 typedef GemmTile<256, 64, 64, 4, 1> TileHead64;  // one 64-wide head per workgroup, wave tile 64(m) x 64(n)
 
+// Kernels that take more than 64 KiB of dynamic LDS need the attribute set once; kernels of the same
+// signature share this function's statics, so the ones already done are kept by address.
 template <class T, class K, class Args>
 void launch(K kernel, const Args &a, int ntiles, hipStream_t st) {
-  static bool attr_set = false;
-  if (!attr_set) {
-    (void)hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, T::SMEM);
-    attr_set = true;
+  static const void *done[8] = {};
+  const void *fn = (const void *)kernel;
+  bool seen = false;
+  int free_slot = -1;
+  for (int i = 0; i < 8; ++i) {
+    if (done[i] == fn) seen = true;
+    else if (!done[i] && free_slot < 0) free_slot = i;
+  }
+  if (!seen) {
+    (void)hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, T::SMEM);
+    if (free_slot >= 0) done[free_slot] = fn;
   }
   kernel<<<ntiles, T::NT, T::SMEM, st>>>(a);
 }
@@ -880,9 +954,12 @@ void launch_proj_gemm(const Dims &d, const gta_weights &w, const void *x, int M,
   }
 }
 
+static bool skinny_wide_tiles(const Dims &d) { return !(d.wq_w % 128 || d.wk_w % 128 || d.wc_w % 128 || d.wg_w % 128); }
+
 int skinny_ksplit(const Dims &d, int M) {
   const int ktiles = d.H / 64;
-  const int tiles = (d.wtot / 128) * ((M + 63) / 64);
+  const int bn = skinny_wide_tiles(d) ? 128 : 64;
+  const int tiles = (d.wtot / bn) * ((M + 63) / 64);
   int want = (768 + tiles - 1) / tiles;
   if (want > 8) want = 8;
   int ks = 1;
@@ -900,10 +977,12 @@ void launch_skinny_proj(const Dims &d, const gta_weights &w, const void *x, int 
   const int wd[4] = {d.wq_w, d.wk_w, d.wc_w, d.wg_w};
   for (int i = 0; i < 4; ++i) { a.w[i] = (const bf16 *)wm[i]; a.width[i] = wd[i]; }
   a.part = part; a.ksplit = ksplit; a.wtot = d.wtot;
-  if (M <= 32) {
-    launch<TileSkinny32>(skinny_proj_kernel<TileSkinny32>, a, ksplit * (d.wtot / 128) * ((M + 31) / 32), st);
-  } else {
-    launch<TileSkinny64>(skinny_proj_kernel<TileSkinny64>, a, ksplit * (d.wtot / 128) * ((M + 63) / 64), st);
+  if (skinny_wide_tiles(d)) {
+    if (M <= 32) launch<TileSkinny32>(skinny_proj_kernel<TileSkinny32>, a, ksplit * (d.wtot / 128) * ((M + 31) / 32), st);
+    else launch<TileSkinny64>(skinny_proj_kernel<TileSkinny64>, a, ksplit * (d.wtot / 128) * ((M + 63) / 64), st);
+  } else {   // every width is a multiple of 64
+    if (M <= 32) launch<TileSkinny32N64>(skinny_proj_kernel<TileSkinny32N64>, a, ksplit * (d.wtot / 64) * ((M + 31) / 32), st);
+    else launch<TileSkinny64N64>(skinny_proj_kernel<TileSkinny64N64>, a, ksplit * (d.wtot / 64) * ((M + 63) / 64), st);
   }
 }
 
@@ -918,7 +997,11 @@ void launch_decoder_gemm(const Dims &d, const void *L, const void *wp, const voi
     else launch<TileBig>(decoder_pair_kernel<TileBig, false>, a, (d.nh / 2) * ((M + 255) / 256), st);
     return;
   }
-  if (d.dh % 128 == 0) {
+  if ((d.dh == 64 || d.dh == 128) && d.hpq % (256 / d.dh) == 0) {
+    const int nt = (d.nh * d.dh / 256) * ((M + 255) / 256);
+    if (d.gate) launch<TileBig>(decoder_multi_kernel<TileBig, true>, a, nt, st);
+    else launch<TileBig>(decoder_multi_kernel<TileBig, false>, a, nt, st);
+  } else if (d.dh % 128 == 0) {
     launch<TileHead>(decoder_gemm_kernel<TileHead>, a, d.nh * (d.dh / 128) * ((M + 255) / 256), st);
   } else {   // heads of 64: one head per 64-wide tile
     launch<TileHead64>(decoder_gemm_kernel<TileHead64>, a, d.nh * (d.dh / 64) * ((M + 255) / 256), st);

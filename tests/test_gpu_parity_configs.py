@@ -101,11 +101,17 @@ def test_config5_varlen_prefill_bf16():
     _check_prefill_workload(wl, full_seqs=[int(order[0])], sampled_seqs=[int(order[-1]), int(order[7])])
 
 
-@pytest.mark.parametrize("shape", ["1b", "wide"])
+@pytest.mark.parametrize("shape", ["1b", "wide", "paper", "paper_nq3"])
 def test_tuned_decode_ragged_contexts(shape):
-    """The streaming decode kernels on ragged context lengths incl. 0, 1, block tails and empty
-    splits, every output element against the oracle."""
-    base = W.WORKLOADS[2] if shape == "1b" else W.scaled(W.WORKLOADS[4], kind="decode", min_seqlen=None)
+    """The streaming decode kernels (wide rows, and the narrow-row kernel of the paper's own layer
+    shapes) on ragged context lengths incl. 0, 1, block tails and empty splits, every output element
+    against the oracle."""
+    if shape == "paper":
+        base = W.PAPER_WORKLOADS[1]
+    elif shape == "paper_nq3":   # the 160M-class layer: 12 heads of 64 in 3 groups
+        base = W.scaled(W.PAPER_WORKLOADS[1], d_model=768, n_heads=12, n_qgroups=3)
+    else:
+        base = W.WORKLOADS[2] if shape == "1b" else W.scaled(W.WORKLOADS[4], kind="decode", min_seqlen=None)
     ctx = [0, 1, 7, 8, 31, 32, 33, 255, 777, 1500]
     wl = W.scaled(base, batch=len(ctx), seqlen=max(ctx))
     assert B.gta_uses_tuned_kernels(B.config_of(wl), B.GTA_MODE_DECODE) == 1
