@@ -8,6 +8,9 @@ The headline metric names two things, so both are measured in every run:
     gta_prefill call and fraction of the bf16 MFMA peak -- under the key "prefill".
 The batched decode workload (B=64, 8192 cached tokens) is reported under "decode_b64_8k" and the
 ragged packed prefill (16 sequences of 512..16384 tokens, H=4096, d_l=1024) under "varlen_prefill".
+"paper_layer_gta1b" holds one attention layer of the paper's own GTA-1B model (H=1280, 20 heads of 64
+in 5 groups, one shared key, one latent of 128) at the batch sizes of its efficiency runs: prefill of
+32 x 2048 tokens and a decode step at batch 64 with 2048 cached tokens.
 
 A "step" is one library call (gta_decode or gta_prefill) on inputs already resident in HBM.
 `roofline` objects are for the dominant kernel of each path, timed live with HIP events around
@@ -280,7 +283,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--only", choices=["decode32k", "decode8k", "prefill", "varlen"], default=None,
+    ap.add_argument("--only", choices=["decode32k", "decode8k", "prefill", "varlen", "paper"], default=None,
                     help="measure one workload only (profiling runs)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run calibration_copy_kernel once on 512 MiB (reads 512 MiB, writes 512 MiB): "
@@ -301,7 +304,7 @@ def main():
         B.gta_calibration_copy(src, dst, 512 << 20)
         torch.cuda.synchronize()
         del src, dst
-    dec = pre = dec8 = var = None
+    dec = pre = dec8 = var = pap = None
     if args.only in (None, "decode32k"):
         dec = bench_decode(W.by_name("decode_b8_32k_bf16"), args.steps, args.warmup, cpu)
     if args.only in (None, "prefill"):
@@ -310,7 +313,12 @@ def main():
         dec8 = bench_decode(W.by_name("decode_b64_8k_bf16"), args.steps, args.warmup, False)
     if args.only in (None, "varlen"):   # ragged packed batch, 16 sequences of 512..16384 tokens, wider model
         var = bench_prefill(W.by_name("varlen_prefill_bf16"), min(args.steps, 10), min(args.warmup, 3), False)
-    main_res = dec or pre or dec8 or var
+    if args.only in (None, "paper"):    # one attention layer of the paper's GTA-1B model (heads of 64, d_l = 128)
+        pap = {"prefill": bench_prefill(W.by_name("gta1b_prefill_b32_t2048"), args.steps, args.warmup, False),
+               "decode": bench_decode(W.by_name("gta1b_decode_b64_t2048"), args.steps, args.warmup, False)}
+        pap["prefill"]["roofline"]["kernel"] = "attn_prefill_kernel (heads of 64, latent 128)"
+        pap["decode"]["roofline"]["kernel"] = "decode_narrow_kernel"
+    main_res = dec or pre or dec8 or var or pap["prefill"]
     line = {
         "metric": "GTA decode HBM GB/s & us/token @32K ctx; prefill bf16 TFLOP/s (% of peak)",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "higher_is_better": True, "scaling": "weak",
@@ -334,6 +342,8 @@ def main():
         line["decode_b64_8k"] = dec8
     if var is not None and main_res is not var:
         line["varlen_prefill"] = var
+    if pap is not None:
+        line["paper_layer_gta1b"] = pap if main_res is not pap["prefill"] else {"decode": pap["decode"]}
     print(json.dumps(line))
 
 

@@ -442,7 +442,7 @@ __global__ __launch_bounds__(256) void decode_narrow_kernel(DecAttnArgs a, RopeF
   }
   const int nblk = (j1 - j0 + R - 1) / R;   // j1 - j0 may be 0 (only the new row)
   struct Blk { u32x4 k, c0, c1; };
-  Blk bA, bB;
+  Blk bA, bB, bC, bD;   // four steps (3 KiB each) in flight per wave
   auto load = [&](Blk &bk, int blk) {   // rows past the slice re-read its last row; weight 0
     const int jb = j0 + blk * R;
     bk.k = __builtin_nontemporal_load(Kp + (int64_t)min(jb + (lane >> 3), j1 - 1) * KROW + (lane & 7));
@@ -480,6 +480,8 @@ __global__ __launch_bounds__(256) void decode_narrow_kernel(DecAttnArgs a, RopeF
   __builtin_amdgcn_sched_barrier(0);
   if (wave < nblk) load(bA, wave);
   if (wave + kWaves < nblk) load(bB, wave + kWaves);
+  if (wave + 2 * kWaves < nblk) load(bC, wave + 2 * kWaves);
+  if (wave + 3 * kWaves < nblk) load(bD, wave + 3 * kWaves);
   __builtin_amdgcn_sched_barrier(0);
   if (q_thread) {
     if (a.praw) rotate(q_lo, q_hi, tid % half);
@@ -542,16 +544,20 @@ __global__ __launch_bounds__(256) void decode_narrow_kernel(DecAttnArgs a, RopeF
       for (int e = 0; e < 8; ++e) acc[g][e] = fmaf(pB, c1[e], fmaf(pA, c0[e], acc[g][e] * cr));
     }
   };
-  auto nvalid = [&](int blk) { return min(R, j1 - (j0 + blk * R)); };
   int blk = wave;
+  auto step = [&](Blk &bk) {   // consume a buffer, then refill it with the step four rounds ahead
+    compute(bk, min(R, j1 - (j0 + blk * R)));
+    if (blk + 4 * kWaves < nblk) load(bk, blk + 4 * kWaves);
+    blk += kWaves;
+  };
   while (blk < nblk) {
-    if (blk != wave && blk + kWaves < nblk) load(bB, blk + kWaves);   // the first pair is already in flight
-    compute(bA, nvalid(blk));
-    blk += kWaves;
+    step(bA);
     if (blk >= nblk) break;
-    if (blk + kWaves < nblk) load(bA, blk + kWaves);
-    compute(bB, nvalid(blk));
-    blk += kWaves;
+    step(bB);
+    if (blk >= nblk) break;
+    step(bC);
+    if (blk >= nblk) break;
+    step(bD);
   }
   if (has_new && wave == 0) {   // the new token's own row, from LDS: one more step with a single valid row
     const u32x4 *nr = reinterpret_cast<const u32x4 *>(newrow);
@@ -733,47 +739,48 @@ __global__ __launch_bounds__(512) void decode_tail_kernel(Dims d, const float *_
     }
   }
   __syncthreads();
-  // combined group output: thread = (4 columns, one of 4 split phases); 8 independent 16-byte loads
-  // in flight per thread, the 4 phases are summed through LDS
+  // combined group output: the (row, 4-column group) items are dealt to the threads, with up to 4
+  // threads per item that split the sum over the splits (summed through LDS); 8 independent 16-byte
+  // loads in flight per thread, all rows of the workgroup in the same round trip
   const int64_t as4 = (int64_t)d.nq * d.dl / 4;
-  const int nc4 = d.dl / 4;
-  float4 *red4 = reinterpret_cast<float4 *>(red);          // [4 phases][nc4], reused below
-  for (int r = 0; r < ROWS; ++r) {
-    const int b = b0 + r;
-    const bool live = b < batch && oldlen[b] >= 0;
-    for (int c0 = 0; c0 < nc4; c0 += 128) {
-      const int c4 = c0 + (tid & 127), ph = tid >> 7;
-      float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (live && c4 < nc4) {
-        const float4 *pa = reinterpret_cast<const float4 *>(pacc + ((int64_t)b * splits * d.nq + g) * d.dl) + c4;
-        const float *w = wt + r * splits;
-        for (int s0 = ph; s0 < splits; s0 += 32) {
-          float4 v[8];
-          float ww[8];
+  const int nc4 = d.dl / 4, items = ROWS * nc4;
+  const int P = items >= 512 ? 1 : (items >= 256 ? 2 : 4);   // phases
+  const int per_pass = 512 / P;                               // items per pass
+  float4 *red4 = reinterpret_cast<float4 *>(red);             // [P][per_pass], reused below
+  for (int base = 0; base < items; base += per_pass) {
+    const int idx = tid % per_pass, ph = tid / per_pass, it = base + idx;
+    const int r = it / nc4, c4 = it % nc4, b = b0 + r;
+    float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (it < items && b < batch && oldlen[b] >= 0) {
+      const float4 *pa = reinterpret_cast<const float4 *>(pacc + ((int64_t)b * splits * d.nq + g) * d.dl) + c4;
+      const float *w = wt + r * splits;
+      for (int s0 = ph; s0 < splits; s0 += 8 * P) {
+        float4 v[8];
+        float ww[8];
 #pragma unroll
-          for (int u = 0; u < 8; ++u) {
-            const int s = s0 + 4 * u;
-            ww[u] = s < splits ? w[s] : 0.f;
-            v[u] = ww[u] != 0.f ? pa[s * as4] : make_float4(0.f, 0.f, 0.f, 0.f);
-          }
+        for (int u = 0; u < 8; ++u) {
+          const int s = s0 + P * u;
+          ww[u] = s < splits ? w[s] : 0.f;
+          v[u] = ww[u] != 0.f ? pa[s * as4] : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
 #pragma unroll
-          for (int u = 0; u < 8; ++u) {
-            a.x = fmaf(ww[u], v[u].x, a.x); a.y = fmaf(ww[u], v[u].y, a.y);
-            a.z = fmaf(ww[u], v[u].z, a.z); a.w = fmaf(ww[u], v[u].w, a.w);
-          }
+        for (int u = 0; u < 8; ++u) {
+          a.x = fmaf(ww[u], v[u].x, a.x); a.y = fmaf(ww[u], v[u].y, a.y);
+          a.z = fmaf(ww[u], v[u].z, a.z); a.w = fmaf(ww[u], v[u].w, a.w);
         }
       }
-      red4[ph * 128 + (tid & 127)] = a;
-      __syncthreads();
-      if (tid < 128 && c4 < nc4) {
-        const float4 x0 = red4[tid], x1 = red4[128 + tid], x2 = red4[256 + tid], x3 = red4[384 + tid];
-        float4 o;
-        o.x = (x0.x + x1.x) + (x2.x + x3.x); o.y = (x0.y + x1.y) + (x2.y + x3.y);
-        o.z = (x0.z + x1.z) + (x2.z + x3.z); o.w = (x0.w + x1.w) + (x2.w + x3.w);
-        reinterpret_cast<float4 *>(Ls + r * d.dl)[c4] = o;
-      }
-      __syncthreads();
     }
+    red4[ph * per_pass + idx] = a;
+    __syncthreads();
+    if (ph == 0 && it < items) {
+      float4 o = red4[idx];
+      for (int q = 1; q < P; ++q) {
+        const float4 x = red4[q * per_pass + idx];
+        o.x += x.x; o.y += x.y; o.z += x.z; o.w += x.w;
+      }
+      reinterpret_cast<float4 *>(Ls + r * d.dl)[c4] = o;
+    }
+    __syncthreads();
   }
   // decoder: thread = (8 output columns, one of 512*8/d_h latent phases); all its weight loads
   // (16 bytes each) are independent; phases are summed by shuffles and through LDS

@@ -65,6 +65,22 @@ struct AttnArgs {
   const int32_t *cu; int per_seq;
   int nq, qpk, qpc, wq_w, wk_w, wc_w, dl, n_qtiles, ndlc, batch;
   float scale_log2e;
+  // fused value decoder (kernel template flag): O_i = (L_g W_{P,i}) * Sigmoid(gate) for the heads of g
+  const bf16 *wp, *gate;     // [n_h, d_l, d_h]; gate pre-activations [total, n_h*d_h] or NULL (gate off)
+  bf16 *out; int hpq, dh, nh;   // [total, n_h*d_h]
+};
+
+// LDS of the fused value decoder: the normalised 256 x DLW tile (row operand) and the DLW x 256
+// decoder matrices of the group's heads side by side; afterwards the 256 x 256 gate / output tile.
+template <class T>
+struct FusedDecoder {
+  static constexpr int N = 256;                         // heads per group x d_h
+  static constexpr int W_PITCH = N * 2 + 64;            // == 64 mod 256 for the transpose reads
+  static constexpr int W_OFF = T::BQ * T::OUT_PITCH;    // behind the L tile
+  static constexpr int G_PITCH = N * 2 + 16;
+  static constexpr int SMEM_LW = W_OFF + T::DLW * W_PITCH, SMEM_G = T::BQ * G_PITCH;
+  static constexpr int SMEM = SMEM_LW > SMEM_G ? (SMEM_LW > T::SMEM ? SMEM_LW : T::SMEM) : (SMEM_G > T::SMEM ? SMEM_G : T::SMEM);
+  static_assert(SMEM <= 160 * 1024, "LDS budget");
 };
 
 constexpr float kLazyThreshold = 8.0f;   // log2 units
@@ -79,7 +95,7 @@ __device__ __forceinline__ float pair_sum(float v) {
   return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
-template <class T>
+template <class T, bool FUSE>
 __global__ __launch_bounds__(T::NT) void attn_prefill_kernel(AttnArgs a) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const int tid = threadIdx.x, lane = tid & 63, h = lane >> 5, ln = lane & 31;
@@ -350,6 +366,92 @@ __global__ __launch_bounds__(T::NT) void attn_prefill_kernel(AttnArgs a) {
         *reinterpret_cast<bf16x4 *>(smem + row * T::OUT_PITCH + (dlb * 32 + rq * 8 + 4 * h) * 2) = v;
       }
   }
+  if constexpr (FUSE) {
+    // ---- value decoder on the tile (Sec. 3.2): the workgroup holds the whole latent width of its
+    // group, so the heads of the group are finished here and L never goes to memory
+    typedef FusedDecoder<T> F;
+    constexpr int WCH = T::DLW * (F::N / 8) / T::NT;     // 16-byte chunks of the decoder matrices per thread
+    constexpr int GCH = T::BQ * (F::N / 8) / T::NT;      // chunks of the gate / output tile per thread
+    const int head0 = g * a.hpq;
+    const int64_t ldo = (int64_t)a.nh * a.dh;
+    u32x4 wr[WCH];
+#pragma unroll
+    for (int i = 0; i < WCH; ++i) {
+      const int c = tid + i * T::NT, k = c / (F::N / 8), col = (c % (F::N / 8)) * 8;
+      wr[i] = *reinterpret_cast<const u32x4 *>(a.wp + ((int64_t)(head0 + col / a.dh) * a.dl + k) * a.dh + col % a.dh);
+    }
+#pragma unroll
+    for (int i = 0; i < WCH; ++i) {
+      const int c = tid + i * T::NT, k = c / (F::N / 8), col = (c % (F::N / 8)) * 8;
+      *reinterpret_cast<u32x4 *>(smem + F::W_OFF + k * F::W_PITCH + col * 2) = wr[i];
+    }
+    // gate tile: requested now, parked in LDS once the operands are dead (rows past the sequence
+    // re-read its last row; they are not stored)
+    const int gr0 = tid / (F::N / 8), gch = tid % (F::N / 8);
+    constexpr int GRPP = T::NT / (F::N / 8);
+    u32x4 gt[GCH];
+    if (a.gate) {
+      const bf16 *gp = a.gate + head0 * a.dh + gch * 8;
+#pragma unroll
+      for (int i = 0; i < GCH; ++i)
+        gt[i] = *reinterpret_cast<const u32x4 *>(gp + (start + min(q0 + i * GRPP + gr0, Tb - 1)) * ldo);
+    }
+    __syncthreads();
+    f32x16 z[F::N / 32];
+#pragma unroll
+    for (int tn = 0; tn < F::N / 32; ++tn)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) z[tn][r] = 0.f;
+    const char *lrow = smem + (wave * 32 + ln) * T::OUT_PITCH + h * 16;
+    const char *wfr = smem + F::W_OFF + (h * 8 + ((lane & 15) >> 2)) * F::W_PITCH + (((lane >> 4) & 1) * 16 + (lane & 3) * 4) * 2;
+#pragma unroll
+    for (int ks = 0; ks < T::DLW / 16; ++ks) {
+      const bf16x8 xf = *reinterpret_cast<const bf16x8 *>(lrow + ks * 32);
+#pragma unroll
+      for (int tn = 0; tn < F::N / 32; ++tn) {
+        const char *wp = wfr + ks * 16 * F::W_PITCH + tn * 64;
+        s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(wp));
+        s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(wp + 4 * F::W_PITCH));
+        s16x8 w8 = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        z[tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, w8), xf, z[tn], 0, 0, 0);
+      }
+    }
+    __syncthreads();   // operands dead: the same LDS now takes the gate tile in output layout
+    if (a.gate) {
+#pragma unroll
+      for (int i = 0; i < GCH; ++i)
+        *reinterpret_cast<u32x4 *>(smem + (i * GRPP + gr0) * F::G_PITCH + gch * 16) = gt[i];
+      __syncthreads();
+    }
+    // lane: row wave*32 + ln, columns tn*32 + rq*8 + 4h .. +3
+    char *orow = smem + (wave * 32 + ln) * F::G_PITCH + 4 * h * 2;
+#pragma unroll
+    for (int tn = 0; tn < F::N / 32; ++tn)
+#pragma unroll
+      for (int rq = 0; rq < 4; ++rq) {
+        bf16x4 *slot = reinterpret_cast<bf16x4 *>(orow + (tn * 32 + rq * 8) * 2);
+        float v[4] = {z[tn][rq * 4], z[tn][rq * 4 + 1], z[tn][rq * 4 + 2], z[tn][rq * 4 + 3]};
+        if (a.gate) {
+          const bf16x4 gz = *slot;
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+            v[i] *= __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * (float)gz[i]));
+        }
+        bf16x4 o;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) o[i] = (bf16)v[i];
+        *slot = o;
+      }
+    __syncthreads();
+    bf16 *Ob = a.out + (start + q0) * ldo + head0 * a.dh + gch * 8;
+#pragma unroll 4
+    for (int i = 0; i < GCH; ++i) {
+      const int r = i * GRPP + gr0;
+      if (q0 + r < Tb)
+        *reinterpret_cast<u32x4 *>(Ob + (int64_t)r * ldo) = *reinterpret_cast<const u32x4 *>(smem + r * F::G_PITCH + gch * 16);
+    }
+    return;
+  }
   __syncthreads();
   bf16 *Lb = a.L + (start + q0) * (int64_t)(a.nq * a.dl) + g * a.dl + dlc * T::DLW;
   constexpr int CPR = T::DLW / 8, RPP = T::NT / CPR;   // 16-byte chunks per output row, rows per pass
@@ -366,17 +468,19 @@ __global__ __launch_bounds__(T::NT) void attn_prefill_kernel(AttnArgs a) {
 typedef AttnTile<128, 256> AttnWide;     // d_h = 128, latent width a multiple of 256
 typedef AttnTile<64, 128> AttnNarrow;    // d_h = 64, latent width a multiple of 128
 
-template <class T>
+template <class T, bool FUSE>
 void launch_attn(const AttnArgs &a0, const Dims &d, int batch, int max_len, hipStream_t st) {
   AttnArgs a = a0;
   a.n_qtiles = (max_len + T::BQ - 1) / T::BQ;
   a.ndlc = d.dl / T::DLW;
+  int smem = T::SMEM;
+  if constexpr (FUSE) smem = FusedDecoder<T>::SMEM;
   static bool attr_set = false;
   if (!attr_set) {
-    (void)hipFuncSetAttribute((const void *)attn_prefill_kernel<T>, hipFuncAttributeMaxDynamicSharedMemorySize, T::SMEM);
+    (void)hipFuncSetAttribute((const void *)attn_prefill_kernel<T, FUSE>, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     attr_set = true;
   }
-  attn_prefill_kernel<T><<<a.n_qtiles * a.ndlc * d.nq * batch, T::NT, T::SMEM, st>>>(a);
+  attn_prefill_kernel<T, FUSE><<<a.n_qtiles * a.ndlc * d.nq * batch, T::NT, smem, st>>>(a);
 }
 
 }  // namespace
@@ -388,16 +492,37 @@ bool attn_prefill_supported(const Dims &d, int max_len) {
   return (d.dh == 128 && d.dl % 256 == 0) || (d.dh == 64 && d.dl % 128 == 0);
 }
 
-void launch_attn_prefill_bf16(const Dims &d, const void *q, const void *k, const void *c, const int32_t *cu,
-                              int batch, int64_t total, int max_len, void *L, hipStream_t st) {
+static AttnArgs attn_args(const Dims &d, const void *q, const void *k, const void *c, const int32_t *cu, int batch,
+                          int64_t total) {
   AttnArgs a{};
-  a.q = (const bf16 *)q; a.k = (const bf16 *)k; a.c = (const bf16 *)c; a.L = (bf16 *)L;
+  a.q = (const bf16 *)q; a.k = (const bf16 *)k; a.c = (const bf16 *)c;
   a.cu = cu; a.per_seq = (int)(total / batch);
   a.nq = d.nq; a.qpk = d.qpk; a.qpc = d.qpc; a.wq_w = d.wq_w; a.wk_w = d.wk_w; a.wc_w = d.wc_w; a.dl = d.dl;
   a.scale_log2e = d.scale * 1.4426950408889634f;
   a.batch = batch;
-  if (d.dh == 128) launch_attn<AttnWide>(a, d, batch, max_len, st);
-  else launch_attn<AttnNarrow>(a, d, batch, max_len, st);
+  return a;
+}
+
+void launch_attn_prefill_bf16(const Dims &d, const void *q, const void *k, const void *c, const int32_t *cu,
+                              int batch, int64_t total, int max_len, void *L, hipStream_t st) {
+  AttnArgs a = attn_args(d, q, k, c, cu, batch, total);
+  a.L = (bf16 *)L;
+  if (d.dh == 128) launch_attn<AttnWide, false>(a, d, batch, max_len, st);
+  else launch_attn<AttnNarrow, false>(a, d, batch, max_len, st);
+}
+
+// One workgroup covers the whole latent width and the group's heads fill one 256-wide tile
+bool attn_decoder_fusable(const Dims &d, int max_len) {
+  return attn_prefill_supported(d, max_len) && d.dh == 64 && d.dl == AttnNarrow::DLW && d.hpq * d.dh == 256;
+}
+
+void launch_attn_decoder_bf16(const Dims &d, const void *q, const void *k, const void *c, const int32_t *cu,
+                              int batch, int64_t total, int max_len, const void *wp, const void *gate, void *out,
+                              hipStream_t st) {
+  AttnArgs a = attn_args(d, q, k, c, cu, batch, total);
+  a.wp = (const bf16 *)wp; a.gate = d.gate ? (const bf16 *)gate : nullptr; a.out = (bf16 *)out;
+  a.hpq = d.hpq; a.dh = d.dh; a.nh = d.nh;
+  launch_attn<AttnNarrow, true>(a, d, batch, max_len, st);
 }
 
 }  // namespace gta

@@ -35,5 +35,10 @@ void launch_plain_gemm(const void *A, int64_t lda, int M, int N, int K, const vo
 bool attn_prefill_supported(const Dims &d, int max_len);
 void launch_attn_prefill_bf16(const Dims &d, const void *q, const void *k, const void *c, const int32_t *cu,
                               int batch, int64_t total, int max_len, void *L, hipStream_t st);
+// attention with the value decoder and gate fused into its epilogue (narrow shapes): writes the heads
+bool attn_decoder_fusable(const Dims &d, int max_len);
+void launch_attn_decoder_bf16(const Dims &d, const void *q, const void *k, const void *c, const int32_t *cu,
+                              int batch, int64_t total, int max_len, const void *wp, const void *gate, void *out,
+                              hipStream_t st);
 
 }  // namespace gta

@@ -12,16 +12,18 @@ int tuned_prefill(const Dims &d, const gta_weights &w, const void *x, const int3
   launch_prefill_setup(d, cu, batch, total, max_len, ws.seq_id, ws.pos, ws.rope, cache, slots, st);
   // Sec. 3.2 projections + App. B.1.1 RoPE + cache write, one MFMA GEMM
   launch_proj_gemm(d, w, x, M, ws, cache, slots, max_len, st);
-  // Sec. 3.3: one causal softmax map per group applied to the latent values
-  if (attn_prefill_supported(d, max_len)) launch_attn_prefill_bf16(d, ws.q, ws.k, ws.c, cu, batch, total, max_len, ws.l, st);
-  else launch_attn_prefill_rowwise(d, ws.q, ws.k, ws.c, cu, batch, total, max_len, ws.l, st);
-  // Sec. 3.2 value decoder with the gate in the epilogue, then the optional W_O
-  if (w.wo) {
-    launch_decoder_gemm(d, ws.l, w.wp, ws.g, ws.o, M, st);
-    launch_plain_gemm(ws.o, d.wg_w, M, d.H, d.wg_w, w.wo, out, st);
+  void *heads = w.wo ? ws.o : out;   // gated heads [M, n_h*d_h]
+  if (attn_decoder_fusable(d, max_len)) {
+    // Sec. 3.3 with the Sec. 3.2 value decoder and gate in the attention kernel's epilogue
+    launch_attn_decoder_bf16(d, ws.q, ws.k, ws.c, cu, batch, total, max_len, w.wp, ws.g, heads, st);
   } else {
-    launch_decoder_gemm(d, ws.l, w.wp, ws.g, out, M, st);
+    // Sec. 3.3: one causal softmax map per group applied to the latent values
+    if (attn_prefill_supported(d, max_len)) launch_attn_prefill_bf16(d, ws.q, ws.k, ws.c, cu, batch, total, max_len, ws.l, st);
+    else launch_attn_prefill_rowwise(d, ws.q, ws.k, ws.c, cu, batch, total, max_len, ws.l, st);
+    // Sec. 3.2 value decoder with the gate in the epilogue
+    launch_decoder_gemm(d, ws.l, w.wp, ws.g, heads, M, st);
   }
+  if (w.wo) launch_plain_gemm(ws.o, d.wg_w, M, d.H, d.wg_w, w.wo, out, st);   // Sec. 3.3 output projection
   return check_launch();
 }
 
