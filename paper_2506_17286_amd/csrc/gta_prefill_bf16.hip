@@ -53,8 +53,8 @@ struct AttnTile {
   // 16-byte chunks per tile row, tile rows one pass of the 512 threads covers, passes per tile
   static constexpr int K_CPR = DH / 8, C_CPR = DLW / 8, K_CHUNKS = BK * K_CPR;
   static constexpr int C_RPP = NT / C_CPR, C_LOADS = BK / C_RPP;
-  // the hand-scheduled main loop below is written for this shape; others take the plain loop
-  static constexpr bool PIPELINED = DH == 128 && DLW == 256;
+  // the hand-scheduled main loop deals 16 softmax slices over 2 * NDLB steps; others take the plain loop
+  static constexpr bool PIPELINED = NDLB == 8 || NDLB == 4;
   static_assert(DH % 16 == 0 && DLW % 32 == 0 && K_CHUNKS <= NT && BK % C_RPP == 0 && C_LOADS >= 1, "tile");
   static_assert(SMEM <= 160 * 1024, "LDS budget");
 };
@@ -277,50 +277,56 @@ __global__ __launch_bounds__(T::NT) void attn_prefill_kernel(AttnArgs a) {
     f32x16 s;
     scores(smem + nxt, s);
     __builtin_amdgcn_sched_barrier(0);
-    // 16 steps, each one MFMA of block t (latent fragment i, read two steps earlier), the transpose
-    // reads of fragment i+2 and a slice of the softmax arithmetic of block t+1; the scheduling barrier
-    // after every step pins this order, so each MFMA is followed by arithmetic that runs in its shadow
+    // 2 * NDLB steps, each one MFMA of block t (latent fragment i, read two steps earlier), the
+    // transpose reads of fragment i+2 and a slice of the softmax arithmetic of block t+1 (16 slices
+    // dealt evenly over the steps); the scheduling barrier after every step pins this order, so each
+    // MFMA is followed by arithmetic that runs in its shadow
     const char *st = smem + cur;
+    constexpr int NS = 2 * T::NDLB, SPS = 16 / NS;   // steps, softmax slices per step
     auto cread = [&](int i) {
-      const char *cp = st + coff + (i >> 3) * 16 * T::C_PITCH + (i & 7) * 64;
+      const char *cp = st + coff + (i / T::NDLB) * 16 * T::C_PITCH + (i % T::NDLB) * 64;
       s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(cp));
       s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(cp + 8 * T::C_PITCH));
       s16x8 c8 = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
       return __builtin_bit_cast(bf16x8, c8);
     };
-    bf16x8 cf[18], pn[2];
+    bf16x8 cf[NS + 2], pn[2];
     cf[0] = cread(0);
     cf[1] = cread(1);
     float b0, b1, b2, b3, b4, m_new = 0.f, negm = 0.f, ps = 0.f;
     const bf16x2 ones = {(bf16)1.0f, (bf16)1.0f};
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      if (i + 2 < 16) cf[i + 2] = cread(i + 2);
-      acc[i & 7] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cf[i], pf[i >> 3], acc[i & 7], 0, 0, 0);
-      if (i == 0) {
+    auto soft_slice = [&](int k) {
+      if (k == 0) {
         b0 = fmaxf(fmaxf(s[0], s[1]), s[2]); b1 = fmaxf(fmaxf(s[3], s[4]), s[5]); b2 = fmaxf(fmaxf(s[6], s[7]), s[8]);
-      } else if (i == 1) {
+      } else if (k == 1) {
         b3 = fmaxf(fmaxf(s[9], s[10]), s[11]); b4 = fmaxf(fmaxf(s[12], s[13]), s[14]); b0 = fmaxf(fmaxf(b0, b1), s[15]);
-      } else if (i == 2) {
+      } else if (k == 2) {
         b2 = fmaxf(fmaxf(b2, b3), b4);
         b0 = pair_max(fmaxf(b0, b2));
-      } else if (i == 3) {
+      } else if (k == 3) {
         const float m_cand = b0 * a.scale_log2e;
         m_new = m_cand > m_run + kLazyThreshold ? fmaxf(m_run, m_cand) : m_run;
         corr = __builtin_amdgcn_exp2f(m_run - m_new);
         m_run = m_new;
         negm = -m_new;
-      } else if (i < 12) {
-        const int e = (i - 4) * 2;   // elements e, e+1 -> k-slots e%8, e%8+1 of pn[e/8]
+      } else if (k < 12) {
+        const int e = (k - 4) * 2;   // elements e, e+1 -> k-slots e%8, e%8+1 of pn[e/8]
         const float p0 = __builtin_amdgcn_exp2f(fmaf(s[e], a.scale_log2e, negm));
         const float p1 = __builtin_amdgcn_exp2f(fmaf(s[e + 1], a.scale_log2e, negm));
         bf16x2 pk;
         pk[0] = (bf16)p0; pk[1] = (bf16)p1;
         pn[e >> 3][e & 7] = pk[0]; pn[e >> 3][(e & 7) + 1] = pk[1];
         ps = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, ps, false);
-      } else if (i == 12) {
+      } else if (k == 12) {
         l_run = fmaf(l_run, corr, ps);
       }
+    };
+#pragma unroll
+    for (int i = 0; i < NS; ++i) {
+      if (i + 2 < NS) cf[i + 2] = cread(i + 2);
+      acc[i % T::NDLB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cf[i], pf[i / T::NDLB], acc[i % T::NDLB], 0, 0, 0);
+#pragma unroll
+      for (int k = i * SPS; k < (i + 1) * SPS; ++k) soft_slice(k);
       __builtin_amdgcn_sched_barrier(0);
     }
     pf[0] = pn[0]; pf[1] = pn[1];
