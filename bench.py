@@ -181,6 +181,32 @@ def bench_prefill(wl, steps, warmup, want_cpu_baseline):
     return res
 
 
+def bench_attention_comparator(steps):
+    """Causal attention stage alone (gta_prefill_attention) at 32 x 2048 tokens for the paper's GTA-1B layer
+    and for the GQA-1B layer written as the degenerate GTA setting (one map per head, 5 key and 5 value
+    groups, latent width = head width): the measured counterpart of the paper's attention-compute ratio."""
+    import torch
+    from paper_2506_17286_amd import binding as B, workloads as W, costmodel as cm
+    gta = W.by_name("gta1b_prefill_b32_t2048")
+    gqa = W.scaled(gta, name="gqa1b_as_degenerate_gta", n_qgroups=20, n_kgroups=5, n_cgroups=5, latent_dim=64)
+    res = {}
+    for wl in (gta, gqa):
+        cfg = B.config_of(wl)
+        total = wl.batch * wl.seqlen
+        kw, cw = wl.kv_width
+        mk = lambda n: (torch.randn((total, n), device="cuda") * 0.9).to(torch.bfloat16)
+        q, k, c = mk(wl.n_qgroups * wl.head_dim), mk(kw), mk(cw)
+        out = torch.empty((total, wl.n_qgroups * wl.latent_dim), dtype=torch.bfloat16, device="cuda")
+        sec = _event_time(lambda: B.gta_prefill_attention(cfg, q, k, c, None, wl.batch, total, wl.seqlen, out), max(steps, 10))
+        fl = cm.prefill_flops(wl, [wl.seqlen] * wl.batch)["attn"]
+        res[wl.name] = {"us": sec * 1e6, "algorithmic_flops": fl, "tflops": fl / sec / 1e12,
+                        "cache_bytes_per_token": (kw + cw) * 2}
+    a, b = res[gta.name], res[gqa.name]
+    res["gta_over_gqa"] = {"time": a["us"] / b["us"], "attention_flops": a["algorithmic_flops"] / b["algorithmic_flops"],
+                           "cache_bytes": a["cache_bytes_per_token"] / b["cache_bytes_per_token"]}
+    return res
+
+
 def _blas_threads():
     try:
         from threadpoolctl import threadpool_info
@@ -318,6 +344,7 @@ def main():
                "decode": bench_decode(W.by_name("gta1b_decode_b64_t2048"), args.steps, args.warmup, False)}
         pap["prefill"]["roofline"]["kernel"] = "attn_prefill_kernel (heads of 64, latent 128)"
         pap["decode"]["roofline"]["kernel"] = "decode_narrow_kernel"
+        pap["attention_vs_gqa"] = bench_attention_comparator(args.steps)
     main_res = dec or pre or dec8 or var or pap["prefill"]
     line = {
         "metric": "GTA decode HBM GB/s & us/token @32K ctx; prefill bf16 TFLOP/s (% of peak)",
@@ -343,7 +370,7 @@ def main():
     if var is not None and main_res is not var:
         line["varlen_prefill"] = var
     if pap is not None:
-        line["paper_layer_gta1b"] = pap if main_res is not pap["prefill"] else {"decode": pap["decode"]}
+        line["paper_layer_gta1b"] = pap if main_res is not pap["prefill"] else {k: v for k, v in pap.items() if k != "prefill"}
     print(json.dumps(line))
 
 

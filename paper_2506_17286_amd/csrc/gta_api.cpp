@@ -227,7 +227,7 @@ int gta_prefill_attention(const gta_config *cfg, const void *q, const void *k, c
     return GTA_ERR_ALIGN;
   if (total_tokens == 0 || max_seqlen == 0) return GTA_OK;
   hipStream_t st = (hipStream_t)hip_stream;
-  if (tuned_prefill_supported(d) && attn_prefill_supported(d, max_seqlen))
+  if (attn_prefill_supported(d, max_seqlen))
     launch_attn_prefill_bf16(d, q, k, c, cu_seqlens, batch, total_tokens, max_seqlen, l_out, st);
   else
     launch_attn_prefill_rowwise(d, q, k, c, cu_seqlens, batch, total_tokens, max_seqlen, l_out, st);

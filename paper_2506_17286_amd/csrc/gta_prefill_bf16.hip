@@ -46,13 +46,13 @@ template <int DH_, int DLW_>
 struct AttnTile {
   static constexpr int DH = DH_, DLW = DLW_, BK = 32, BQ = 256, NT = 512, NDLB = DLW / 32, NSTAGE = 3;
   static constexpr int K_PITCH = DH * 2 + 16;      // 16 * odd: conflict-free 16-byte row reads
-  static constexpr int C_PITCH = DLW * 2 + 64;     // == 64 mod 256: conflict-free transpose reads
+  static constexpr int C_PITCH = DLW * 2 + 64 + (DLW % 128 ? 128 : 0);   // == 64 mod 256: conflict-free transpose reads
   static constexpr int K_BYTES = BK * K_PITCH, C_BYTES = BK * C_PITCH, STAGE = K_BYTES + C_BYTES;
   static constexpr int OUT_PITCH = DLW * 2 + 16;
   static constexpr int SMEM = BQ * OUT_PITCH > NSTAGE * STAGE ? BQ * OUT_PITCH : NSTAGE * STAGE;
   // 16-byte chunks per tile row, tile rows one pass of the 512 threads covers, passes per tile
   static constexpr int K_CPR = DH / 8, C_CPR = DLW / 8, K_CHUNKS = BK * K_CPR;
-  static constexpr int C_RPP = NT / C_CPR, C_LOADS = BK / C_RPP;
+  static constexpr int C_RPP = NT / C_CPR < BK ? NT / C_CPR : BK, C_LOADS = BK / C_RPP, C_CHUNKS = C_RPP * C_CPR;
   // the hand-scheduled main loop deals 16 softmax slices over 2 * NDLB steps; others take the plain loop
   static constexpr bool PIPELINED = NDLB == 8 || NDLB == 4;
   static_assert(DH % 16 == 0 && DLW % 32 == 0 && K_CHUNKS <= NT && BK % C_RPP == 0 && C_LOADS >= 1, "tile");
@@ -146,24 +146,28 @@ __global__ __launch_bounds__(T::NT) void attn_prefill_kernel(AttnArgs a) {
   // (such keys are in the future of every valid query and are masked)
   u32x4 rk, rc[T::C_LOADS];
   const int k_row = tid / T::K_CPR, k_ch = tid % T::K_CPR, c_row = tid / T::C_CPR, c_ch = tid % T::C_CPR;
-  const bool k_loader = tid < T::K_CHUNKS;   // a narrow key tile has fewer chunks than threads
+  const bool k_loader = tid < T::K_CHUNKS, c_loader = tid < T::C_CHUNKS;   // narrow tiles have fewer chunks than threads
   auto gload = [&](int t) {
     const int j0 = t * T::BK;
     if (k_loader) {
       const unsigned r = min(j0 + k_row, Tb - 1);
       rk = *reinterpret_cast<const u32x4 *>(Kb + (r * wk2 + k_ch * 16));
     }
+    if (c_loader) {
 #pragma unroll
-    for (int i = 0; i < T::C_LOADS; ++i) {
-      const unsigned r = min(j0 + c_row + i * T::C_RPP, Tb - 1);
-      rc[i] = *reinterpret_cast<const u32x4 *>(Cb + (r * wc2 + c_ch * 16));
+      for (int i = 0; i < T::C_LOADS; ++i) {
+        const unsigned r = min(j0 + c_row + i * T::C_RPP, Tb - 1);
+        rc[i] = *reinterpret_cast<const u32x4 *>(Cb + (r * wc2 + c_ch * 16));
+      }
     }
   };
   auto sstore = [&](char *st) {
     if (k_loader) *reinterpret_cast<u32x4 *>(st + k_row * T::K_PITCH + k_ch * 16) = rk;
+    if (c_loader) {
 #pragma unroll
-    for (int i = 0; i < T::C_LOADS; ++i)
-      *reinterpret_cast<u32x4 *>(st + T::K_BYTES + (c_row + i * T::C_RPP) * T::C_PITCH + c_ch * 16) = rc[i];
+      for (int i = 0; i < T::C_LOADS; ++i)
+        *reinterpret_cast<u32x4 *>(st + T::K_BYTES + (c_row + i * T::C_RPP) * T::C_PITCH + c_ch * 16) = rc[i];
+    }
   };
   const int koff = ln * T::K_PITCH + h * 16;
   const int coff = T::K_BYTES + (4 * h + ((lane & 15) >> 2)) * T::C_PITCH + (((lane >> 4) & 1) * 16 + (lane & 3) * 4) * 2;
@@ -473,6 +477,8 @@ __global__ __launch_bounds__(T::NT) void attn_prefill_kernel(AttnArgs a) {
 
 typedef AttnTile<128, 256> AttnWide;     // d_h = 128, latent width a multiple of 256
 typedef AttnTile<64, 128> AttnNarrow;    // d_h = 64, latent width a multiple of 128
+typedef AttnTile<64, 64> AttnSlim;       // d_h = 64, other latent widths that are multiples of 64 (e.g. the
+                                         // GQA-degenerate setting d_l = d_h used as a comparator)
 
 template <class T, bool FUSE>
 void launch_attn(const AttnArgs &a0, const Dims &d, int batch, int max_len, hipStream_t st) {
@@ -495,7 +501,7 @@ bool attn_prefill_supported(const Dims &d, int max_len) {
   // byte offsets inside one sequence's K / C rows are kept in 32 bits
   if ((int64_t)max_len * d.wc_w * 2 >= ((int64_t)1 << 31) || (int64_t)max_len * d.wk_w * 2 >= ((int64_t)1 << 31)) return false;
   if (d.dtype != GTA_BF16 || d.wq_w % 8 || d.wk_w % 8 || d.wc_w % 8) return false;
-  return (d.dh == 128 && d.dl % 256 == 0) || (d.dh == 64 && d.dl % 128 == 0);
+  return (d.dh == 128 && d.dl % 256 == 0) || (d.dh == 64 && d.dl % 64 == 0);
 }
 
 static AttnArgs attn_args(const Dims &d, const void *q, const void *k, const void *c, const int32_t *cu, int batch,
@@ -514,7 +520,8 @@ void launch_attn_prefill_bf16(const Dims &d, const void *q, const void *k, const
   AttnArgs a = attn_args(d, q, k, c, cu, batch, total);
   a.L = (bf16 *)L;
   if (d.dh == 128) launch_attn<AttnWide, false>(a, d, batch, max_len, st);
-  else launch_attn<AttnNarrow, false>(a, d, batch, max_len, st);
+  else if (d.dl % 128 == 0) launch_attn<AttnNarrow, false>(a, d, batch, max_len, st);
+  else launch_attn<AttnSlim, false>(a, d, batch, max_len, st);
 }
 
 // One workgroup covers the whole latent width and the group's heads fill one 256-wide tile

@@ -133,7 +133,7 @@ def test_tuned_decode_ragged_contexts(shape):
 
 
 @pytest.mark.parametrize("shape,with_wo", [("1b", False), ("1b", True), ("wide", False), ("paper", False),
-                                           ("paper", True), ("packed128", False)])
+                                           ("paper", True), ("packed128", False), ("slim", False)])
 def test_tuned_prefill_ragged_small(shape, with_wo):
     """The MFMA prefill path (1B and wide shapes, the paper's own layer shape with heads of 64 and one
     shared key, and a shape with heads of 128 whose tiles straddle the Q | K | C | gate boundaries) on
@@ -143,6 +143,8 @@ def test_tuned_prefill_ragged_small(shape, with_wo):
         base = W.PAPER_WORKLOADS[0]
     elif shape == "packed128":
         base = W.scaled(W.WORKLOADS[1], d_model=512, n_heads=4, n_qgroups=2, n_kgroups=1, n_cgroups=1, latent_dim=128)
+    elif shape == "slim":   # GQA-like: one map per head, latent as wide as a head, several key / latent groups
+        base = W.scaled(W.PAPER_WORKLOADS[0], d_model=512, n_heads=8, n_qgroups=8, n_kgroups=2, n_cgroups=2, latent_dim=64)
     else:
         base = W.WORKLOADS[1] if shape == "1b" else W.WORKLOADS[4]
     lens = [1, 37, 256, 300, 129, 64]
