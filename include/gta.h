@@ -50,7 +50,7 @@ typedef enum {
 
 enum { GTA_F32 = 0, GTA_BF16 = 1 };            /* gta_config.dtype */
 enum { GTA_GATE_SIGMOID = 0, GTA_GATE_OFF = 1 }; /* gta_config.gate  */
-enum { GTA_MODE_PREFILL = 0, GTA_MODE_DECODE = 1 };
+enum { GTA_MODE_PREFILL = 0, GTA_MODE_DECODE = 1, GTA_MODE_PREFILL_CHUNK = 2 };
 
 /* Hyper-parameters of one GTA layer (Sec. 3.2).  Host memory. */
 typedef struct {
@@ -97,6 +97,7 @@ typedef struct {
  *   mode PREFILL: batch sequences, total_tokens packed tokens, longest sequence <= max_len.
  *   mode DECODE : batch sequences, max_len = cache->max_seq, num_splits as passed to gta_decode
  *                 (0 = library's choice).
+ *   mode PREFILL_CHUNK: as PREFILL, for gta_prefill_chunk (max_len = max_chunk).
  * Returns 0 if cfg is NULL or invalid. */
 GTA_API size_t gta_workspace_bytes(const gta_config *cfg, int mode, int32_t batch, int64_t total_tokens,
                            int32_t max_len, int32_t num_splits);
@@ -115,6 +116,22 @@ GTA_API int gta_prefill(const gta_config *cfg, const gta_weights *weights, const
                 const int32_t *cu_seqlens, int32_t batch, int64_t total_tokens,
                 int32_t max_seqlen, const gta_cache *cache, const int32_t *slots, void *out,
                 void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Chunked / prefix prefill: App. B.1.3 (append, then attend over everything cached) for a chunk of
+ * new tokens per sequence instead of one.  Token i of sequence b takes position seq_lens[slot] + i:
+ * q and k are rotated there, k and c are stored as row seq_lens[slot] + i, the token attends over
+ * rows 0 .. seq_lens[slot] + i, and seq_lens[slot] grows by the chunk length.  On an empty slot this
+ * equals gta_prefill; splitting a sequence into chunks of any sizes gives the rows of one prefill.
+ *   x, cu_seqlens, slots, out   as for gta_prefill (lengths are chunk lengths)
+ *   max_chunk   host upper bound of the longest chunk (sizes the launch), <= cache->max_seq
+ *   cache       required.  A sequence whose chunk does not fit (seq_lens + T_b > max_seq) or whose slot
+ *               is out of range stores nothing, gets zero output rows and status GTA_ERR_CACHE_FULL.
+ * Available where gta_uses_tuned_kernels(cfg, GTA_MODE_PREFILL) is 1 and the attention kernel covers
+ * the shape (bf16, d_h 64 or 128); otherwise GTA_ERR_UNSUPPORTED.  Workspace: mode PREFILL_CHUNK. */
+GTA_API int gta_prefill_chunk(const gta_config *cfg, const gta_weights *weights, const void *x,
+                      const int32_t *cu_seqlens, int32_t batch, int64_t total_tokens,
+                      int32_t max_chunk, const gta_cache *cache, const int32_t *slots, void *out,
+                      void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /* One decode step (App. B.1.3) for `batch` sequences: project x_new, rotate q and k at position
  * seq_lens[slot], append k and c as row seq_lens[slot], increment seq_lens[slot], then attend

@@ -15,12 +15,12 @@ LIB_PATH = os.path.join(_HERE, "libgta.so")
 
 GTA_F32, GTA_BF16 = 0, 1
 GTA_GATE_SIGMOID, GTA_GATE_OFF = 0, 1
-GTA_MODE_PREFILL, GTA_MODE_DECODE = 0, 1
+GTA_MODE_PREFILL, GTA_MODE_DECODE, GTA_MODE_PREFILL_CHUNK = 0, 1, 2
 GTA_OK = 0
 GTA_ERR_NULL, GTA_ERR_SHAPE, GTA_ERR_ALIGN, GTA_ERR_DTYPE = -1, -2, -3, -4
 GTA_ERR_UNSUPPORTED, GTA_ERR_WORKSPACE, GTA_ERR_HIP, GTA_ERR_CACHE_FULL = -5, -6, -7, -8
 
-EXPORTS = ["gta_workspace_bytes", "gta_prefill", "gta_decode", "gta_cache_append", "gta_strerror",
+EXPORTS = ["gta_workspace_bytes", "gta_prefill", "gta_prefill_chunk", "gta_decode", "gta_cache_append", "gta_strerror",
            "gta_uses_tuned_kernels", "gta_prefill_attention", "gta_decode_attention", "gta_decode_combine", "gta_calibration_copy",
            "gta_calibration_read", "gta_calibration_mfma"]
 
@@ -69,6 +69,8 @@ def load(path: Optional[str] = None) -> ctypes.CDLL:
     lib.gta_workspace_bytes.argtypes = [cfgp, ctypes.c_int, i32, i64, i32, i32]
     lib.gta_prefill.restype = ctypes.c_int
     lib.gta_prefill.argtypes = [cfgp, wp, vp, vp, i32, i64, i32, cp, vp, vp, vp, sz, vp]
+    lib.gta_prefill_chunk.restype = ctypes.c_int
+    lib.gta_prefill_chunk.argtypes = [cfgp, wp, vp, vp, i32, i64, i32, cp, vp, vp, vp, sz, vp]
     lib.gta_decode.restype = ctypes.c_int
     lib.gta_decode.argtypes = [cfgp, wp, vp, i32, cp, vp, vp, i32, vp, sz, vp]
     lib.gta_cache_append.restype = ctypes.c_int
@@ -160,6 +162,18 @@ def gta_prefill(cfg: gta_config, weights: gta_weights, x, cu_seqlens, batch: int
                             _stream(stream))
     if check:
         _check(rc, "gta_prefill")
+    return rc
+
+
+def gta_prefill_chunk(cfg: gta_config, weights: gta_weights, x, cu_seqlens, batch: int, total_tokens: int,
+                      max_chunk: int, cache: gta_cache, slots, out, workspace, stream=None, check: bool = True) -> int:
+    rc = load().gta_prefill_chunk(ctypes.byref(cfg), ctypes.byref(weights), _ptr(x), _ptr(cu_seqlens), batch,
+                                  total_tokens, max_chunk, ctypes.byref(cache) if cache is not None else None,
+                                  _ptr(slots), _ptr(out), _ptr(workspace),
+                                  0 if workspace is None else workspace.numel() * workspace.element_size(),
+                                  _stream(stream))
+    if check:
+        _check(rc, "gta_prefill_chunk")
     return rc
 
 

@@ -51,14 +51,15 @@ struct Carver {
 };
 }  // namespace
 
-PrefillWs carve_prefill(const Dims &d, bool tuned, bool with_wo, int batch, int64_t total, int max_len, void *base) {
-  (void)batch;
+PrefillWs carve_prefill(const Dims &d, bool tuned, bool with_wo, int batch, int64_t total, int max_len, void *base,
+                        bool chunk) {
   Carver cv(base);
   PrefillWs w{};
   const size_t n = (size_t)total, es = (size_t)d.esize();
   w.seq_id = cv.take<int32_t>(n * 4);
   w.pos = cv.take<int32_t>(n * 4);
-  w.rope = cv.take<float2>(d.rope ? (size_t)max_len * (d.dh / 2) * sizeof(float2) : 0);
+  // RoPE rows: one per position (fresh prefill) or one per packed token (chunked prefill)
+  w.rope = cv.take<float2>(d.rope ? (size_t)(chunk ? total : max_len) * (d.dh / 2) * sizeof(float2) : 0);
   w.praw = cv.take<float>(tuned ? 0 : n * d.wtot * 4);
   w.q = cv.take<void>(n * d.wq_w * es);
   w.k = cv.take<void>(n * d.wk_w * es);
@@ -67,6 +68,7 @@ PrefillWs carve_prefill(const Dims &d, bool tuned, bool with_wo, int batch, int6
   w.l = cv.take<void>(n * (size_t)d.nq * d.dl * (tuned ? es : 4));
   w.o = cv.take<void>(with_wo ? n * d.wg_w * (tuned ? es : 4) : 0);
   w.wpack = cv.take<void>(tuned ? proj_packed_bytes(d) : 0);
+  w.prefix = cv.take<int32_t>(chunk ? (size_t)batch * 4 : 0);
   w.bytes = cv.off;
   return w;
 }
@@ -153,6 +155,8 @@ size_t gta_workspace_bytes(const gta_config *cfg, int mode, int32_t batch, int64
                            int32_t num_splits) {
   Dims d;
   if (make_dims(cfg, &d) != GTA_OK || batch <= 0 || max_len < 0) return 0;
+  if (mode == GTA_MODE_PREFILL_CHUNK)
+    return carve_prefill(d, true, true, batch, total_tokens, max_len, nullptr, true).bytes + 256;
   if (mode == GTA_MODE_PREFILL) {
     if (total_tokens < 0) return 0;
     // sized for a call with W_O (a superset of the call without)
@@ -191,6 +195,30 @@ int gta_prefill(const gta_config *cfg, const gta_weights *weights, const void *x
   if (tuned)
     return tuned_prefill(d, *weights, x, cu_seqlens, batch, total_tokens, max_seqlen, cache, slots, out, ws, st);
   return generic_prefill(d, *weights, x, cu_seqlens, batch, total_tokens, max_seqlen, cache, slots, out, ws, st);
+}
+
+int gta_prefill_chunk(const gta_config *cfg, const gta_weights *weights, const void *x, const int32_t *cu_seqlens,
+                      int32_t batch, int64_t total_tokens, int32_t max_chunk, const gta_cache *cache,
+                      const int32_t *slots, void *out, void *workspace, size_t workspace_bytes, void *hip_stream) {
+  Dims d;
+  int rc = make_dims(cfg, &d);
+  if (rc != GTA_OK) return rc;
+  if ((rc = check_weights(weights)) != GTA_OK) return rc;
+  if (!x || !out || !cache) return GTA_ERR_NULL;
+  if (batch <= 0 || batch > kMaxBatch || total_tokens < 0 || total_tokens > INT32_MAX || max_chunk < 0)
+    return GTA_ERR_SHAPE;
+  if (!cu_seqlens && (total_tokens % batch != 0 || total_tokens / batch > max_chunk)) return GTA_ERR_SHAPE;
+  if ((int64_t)total_tokens * d.wtot > ((int64_t)1 << 40)) return GTA_ERR_UNSUPPORTED;
+  if (misaligned(x) || misaligned(out) || ((uintptr_t)cu_seqlens & 3u) || ((uintptr_t)slots & 3u)) return GTA_ERR_ALIGN;
+  if ((rc = check_cache(cache)) != GTA_OK) return rc;
+  if (max_chunk > cache->max_seq || (!slots && batch > cache->max_batch)) return GTA_ERR_SHAPE;
+  if (!tuned_prefill_chunk_supported(d, cache->max_seq)) return GTA_ERR_UNSUPPORTED;
+  if (total_tokens == 0 || max_chunk == 0) return GTA_OK;
+  if (!workspace || misaligned(workspace)) return GTA_ERR_WORKSPACE;
+  PrefillWs ws = carve_prefill(d, true, weights->wo != nullptr, batch, total_tokens, max_chunk, workspace, true);
+  if (ws.bytes > workspace_bytes) return GTA_ERR_WORKSPACE;
+  return tuned_prefill_chunk(d, *weights, x, cu_seqlens, batch, total_tokens, max_chunk, *cache, slots, out, ws,
+                             (hipStream_t)hip_stream);
 }
 
 int gta_decode(const gta_config *cfg, const gta_weights *weights, const void *x_new, int32_t batch,

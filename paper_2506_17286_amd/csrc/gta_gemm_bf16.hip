@@ -375,6 +375,7 @@ struct ProjArgs {
   bf16 *dst[4];                       // Q, K, C, gate pre-activation  [M, width]
   const int32_t *seq_id, *pos;        // per packed token
   const float2 *rope; int max_len;    // (cos, sin)[pos][j], NULL = no RoPE
+  int rope_by_token;                  // chunked prefill: the table has one row per packed token instead
   int dh;
   bf16 *kcache, *ccache; const int32_t *slots; int max_batch, max_seq;   // kcache NULL = no cache write
 };
@@ -412,7 +413,8 @@ __global__ __launch_bounds__(T::NT) void proj_gemm_kernel(ProjArgs a) {
     const int m = m0 + wm * T::WM + tm * 32 + (lane & 31);
     if (m >= a.M) continue;
     const int p = a.pos[m];
-    if (rotate && p < a.max_len) {
+    const int rrow = a.rope_by_token ? m : p;   // RoPE table row
+    if (rotate && (a.rope_by_token || p < a.max_len)) {
       // wave tile spans whole heads (WN % d_h == 0); pair column j with j + d_h/2 of the same head
       constexpr int tiles_half = kHeadDim / 64, tiles_head = kHeadDim / 32;
 #pragma unroll
@@ -423,7 +425,7 @@ __global__ __launch_bounds__(T::NT) void proj_gemm_kernel(ProjArgs a) {
 #pragma unroll
         for (int rq = 0; rq < 4; ++rq) {
           const int j = (tn % tiles_head) * 32 + rq * 8 + (lane >> 5) * 4;
-          const float4 *tp = reinterpret_cast<const float4 *>(a.rope + (int64_t)p * half + j);
+          const float4 *tp = reinterpret_cast<const float4 *>(a.rope + (int64_t)rrow * half + j);
           const float4 t0 = tp[0], t1 = tp[1];
           const float cs[4] = {t0.x, t0.z, t1.x, t1.z}, sn[4] = {t0.y, t0.w, t1.y, t1.w};
 #pragma unroll
@@ -441,7 +443,7 @@ __global__ __launch_bounds__(T::NT) void proj_gemm_kernel(ProjArgs a) {
     if (cache) {
       const int b = a.seq_id[m];
       const int slot = a.slots ? a.slots[b] : b;
-      if (slot >= 0 && slot < a.max_batch && p < a.max_seq) crow = cache + ((int64_t)slot * a.max_seq + p) * width + nw;
+      if (slot >= 0 && slot < a.max_batch && p >= 0 && p < a.max_seq) crow = cache + ((int64_t)slot * a.max_seq + p) * width + nw;
     }
 #pragma unroll
     for (int tn = 0; tn < T::TN; ++tn)
@@ -465,7 +467,7 @@ __global__ __launch_bounds__(T::NT) void proj_gemm_kernel(ProjArgs a) {
       if (m < a.M) {
         const int p = a.pos[m], b = a.seq_id[m];
         const int slot = a.slots ? a.slots[b] : b;
-        if (slot >= 0 && slot < a.max_batch && p < a.max_seq) cr = (int64_t)slot * a.max_seq + p;
+        if (slot >= 0 && slot < a.max_batch && p >= 0 && p < a.max_seq) cr = (int64_t)slot * a.max_seq + p;
       }
       crow_of[threadIdx.x] = cr;
     }
@@ -521,7 +523,7 @@ __global__ __launch_bounds__(T::NT) void proj_packed_kernel(ProjArgs a, const bf
 #pragma unroll
     for (int tm = 0; tm < T::TM; ++tm) {
       const int m = m0 + wm * T::WM + tm * 32 + (lane & 31);
-      const int p = min(a.pos[min(m, a.M - 1)], a.max_len - 1);
+      const int p = a.rope_by_token ? min(m, a.M - 1) : max(min(a.pos[min(m, a.M - 1)], a.max_len - 1), 0);   // RoPE table row
 #pragma unroll
       for (int tn = 0; tn < T::TN; ++tn) {
         if ((tn % tiles_head) >= tiles_half) continue;
@@ -556,7 +558,7 @@ __global__ __launch_bounds__(T::NT) void proj_packed_kernel(ProjArgs a, const bf
     if (m < a.M) {
       const int p = a.pos[m], b = a.seq_id[m];
       const int slot = a.slots ? a.slots[b] : b;
-      if (slot >= 0 && slot < a.max_batch && p < a.max_seq) cr = (int64_t)slot * a.max_seq + p;
+      if (slot >= 0 && slot < a.max_batch && p >= 0 && p < a.max_seq) cr = (int64_t)slot * a.max_seq + p;
     }
     crow_of[threadIdx.x] = cr;
   }
@@ -918,8 +920,9 @@ size_t proj_packed_bytes(const Dims &d) {
 }
 
 void launch_proj_gemm(const Dims &d, const gta_weights &w, const void *x, int M, const PrefillWs &ws,
-                      const gta_cache *cache, const int32_t *slots, int max_len, hipStream_t st) {
+                      const gta_cache *cache, const int32_t *slots, int max_len, hipStream_t st, bool rope_by_token) {
   ProjArgs a{};
+  a.rope_by_token = rope_by_token ? 1 : 0;
   a.x = (const bf16 *)x; a.lda = d.H; a.M = M; a.K = d.H;
   const void *wm[4] = {w.wq, w.wk, w.wc, w.wg};
   const int wd[4] = {d.wq_w, d.wk_w, d.wc_w, d.wg_w};

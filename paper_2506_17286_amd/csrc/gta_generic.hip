@@ -225,6 +225,71 @@ __global__ void prefill_setup_kernel(const int32_t *cu, int batch, int64_t total
   if (b < batch) prefill_commit_seq(cv, cu, per_seq, b);
 }
 
+// Chunked prefill (a chunk of new tokens behind the rows a slot already holds, App. B.1.3 applied to
+// several tokens at once).  prefix[b] = rows cached before the chunk, or -1 if the slot is invalid or
+// the chunk does not fit (the sequence is then skipped: nothing stored, zero output, status flagged at
+// commit).  Token t of sequence b gets position prefix[b] + (t - cu[b]); the RoPE table is per packed
+// token here (row t), since positions of different sequences no longer coincide.  Blocks [0, nb_row):
+// row map, then nb_rope blocks: RoPE rows, last blocks: prefix[].  Nothing in this launch writes the
+// cached lengths, so every block may read them.
+__device__ __forceinline__ int chunk_prefix(const CacheView &cv, const int32_t *cu, int per_seq, int b) {
+  const int slot = cv.slots ? cv.slots[b] : b;
+  if (slot < 0 || slot >= cv.max_batch) return -1;
+  const int old = cv.seq_lens[slot], n = cu ? cu[b + 1] - cu[b] : per_seq;
+  return (old >= 0 && old + n <= cv.max_seq) ? old : -1;
+}
+
+__global__ void prefill_chunk_setup_kernel(const int32_t *cu, int batch, int64_t total, int per_seq, int32_t *seq_id,
+                                           int32_t *pos, int nb_row, float2 *tab, int half, int dh, double base,
+                                           int nb_rope, CacheView cv, int32_t *prefix) {
+  int blk = blockIdx.x;
+  auto locate = [&](int64_t t, int &b, int &i) {
+    if (!cu) { b = (int)(t / per_seq); i = (int)(t % per_seq); return; }
+    int lo = 0, hi = batch;
+    while (hi - lo > 1) {
+      int mid = (lo + hi) >> 1;
+      if (cu[mid] <= t) lo = mid; else hi = mid;
+    }
+    b = lo; i = (int)(t - cu[lo]);
+  };
+  if (blk < nb_row) {
+    int64_t t = blk * (int64_t)blockDim.x + threadIdx.x;
+    if (t >= total) return;
+    int b, i;
+    locate(t, b, i);
+    const int pre = chunk_prefix(cv, cu, per_seq, b);
+    seq_id[t] = b;
+    pos[t] = pre < 0 ? -1 : pre + i;
+    return;
+  }
+  blk -= nb_row;
+  if (blk < nb_rope) {
+    int64_t e = blk * (int64_t)blockDim.x + threadIdx.x;
+    if (e >= total * half) return;
+    int b, i;
+    locate(e / half, b, i);
+    const int pre = chunk_prefix(cv, cu, per_seq, b), j = (int)(e % half);
+    double ang = (double)(pre < 0 ? 0 : pre + i) * pow(base, -2.0 * (double)j / (double)dh);
+    double sn, cs;
+    sincos(ang, &sn, &cs);
+    tab[e] = make_float2((float)cs, (float)sn);
+    return;
+  }
+  blk -= nb_rope;
+  int b = blk * blockDim.x + threadIdx.x;
+  if (b < batch) prefix[b] = chunk_prefix(cv, cu, per_seq, b);
+}
+
+__global__ void prefill_chunk_commit_kernel(CacheView cv, const int32_t *cu, int batch, int per_seq,
+                                            const int32_t *prefix) {
+  int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= batch) return;
+  const int slot = cv.slots ? cv.slots[b] : b;
+  if (slot < 0 || slot >= cv.max_batch) return;
+  if (prefix[b] >= 0) cv.seq_lens[slot] = prefix[b] + (cu ? cu[b + 1] - cu[b] : per_seq);
+  else cv.status[slot] = GTA_ERR_CACHE_FULL;
+}
+
 // Decode: position = tokens already cached; the new key / latent row is appended at that row.
 template <typename T>
 __global__ void finalize_decode_kernel(Dims d, const float *praw, int nsum, int batch, float *Qo, float *Go,
@@ -629,6 +694,24 @@ void launch_prefill_setup(const Dims &d, const int32_t *cu, int batch, int64_t t
   prefill_setup_kernel<<<nb_row + nb_rope + nb_commit, 256, 0, st>>>(
       cu, batch, total, (int)(total / batch), seq_id, pos, nb_row, tab, max_len, half, d.dh, d.rope_base, nb_rope,
       cache ? view_of(cache, slots) : CacheView{});
+}
+
+void launch_prefill_chunk_setup(const Dims &d, const int32_t *cu, int batch, int64_t total, int32_t *seq_id,
+                                int32_t *pos, float2 *tab, int32_t *prefix, const gta_cache &cache,
+                                const int32_t *slots, hipStream_t st) {
+  if (total <= 0) return;
+  const int half = d.dh / 2;
+  const int nb_row = (int)((total + 255) / 256);
+  const int nb_rope = d.rope && half > 0 ? (int)((total * half + 255) / 256) : 0;
+  prefill_chunk_setup_kernel<<<nb_row + nb_rope + (batch + 255) / 256, 256, 0, st>>>(
+      cu, batch, total, (int)(total / batch), seq_id, pos, nb_row, tab, half, d.dh, d.rope_base, nb_rope,
+      view_of(&cache, slots), prefix);
+}
+
+void launch_prefill_chunk_commit(const gta_cache &cache, const int32_t *slots, const int32_t *cu, int batch,
+                                 int64_t total, const int32_t *prefix, hipStream_t st) {
+  prefill_chunk_commit_kernel<<<grid1d(batch), 256, 0, st>>>(view_of(&cache, slots), cu, batch, (int)(total / batch),
+                                                             prefix);
 }
 
 int generic_prefill(const Dims &d, const gta_weights &w, const void *x, const int32_t *cu, int batch,

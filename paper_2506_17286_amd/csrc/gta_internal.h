@@ -39,10 +39,11 @@ struct PrefillWs {
   void *l;                 // normalised group outputs [total, n_q*d_l]; fp32 (generic) or dtype
   void *o;                 // gated heads [total, wg_w] (dtype), only with W_O
   void *wpack;             // tuned path, some shapes: [W_Q | W_K | W_C | W_G] side by side, [H, wtot]
+  int32_t *prefix;         // chunked prefill: [batch] rows cached before the chunk, or -1 (sequence skipped)
   size_t bytes;
 };
 PrefillWs carve_prefill(const Dims &d, bool tuned, bool with_wo, int batch, int64_t total,
-                        int max_len, void *base);
+                        int max_len, void *base, bool chunk = false);
 
 struct DecodeWs {
   float *praw;             // [ksplit, batch, wtot] raw fp32 projections of the new tokens (split-K partials)
@@ -93,6 +94,12 @@ void launch_rowmap(const int32_t *cu, int batch, int64_t total, int32_t *seq_id,
 void launch_rope_table(float2 *tab, int max_pos, int dh, double base, hipStream_t st);
 void launch_prefill_commit(const gta_cache &cache, const int32_t *slots, const int32_t *cu,
                            int batch, int64_t total, hipStream_t st);
+// chunked prefill: row map with positions behind the cached rows, per-token RoPE rows, prefix[]; commit
+void launch_prefill_chunk_setup(const Dims &d, const int32_t *cu, int batch, int64_t total, int32_t *seq_id,
+                                int32_t *pos, float2 *tab, int32_t *prefix, const gta_cache &cache,
+                                const int32_t *slots, hipStream_t st);
+void launch_prefill_chunk_commit(const gta_cache &cache, const int32_t *slots, const int32_t *cu, int batch,
+                                 int64_t total, const int32_t *prefix, hipStream_t st);
 // row map, RoPE table (if d.rope) and cached lengths (if cache) of one prefill call in one launch
 void launch_prefill_setup(const Dims &d, const int32_t *cu, int batch, int64_t total, int max_len,
                           int32_t *seq_id, int32_t *pos, float2 *tab, const gta_cache *cache,

@@ -68,6 +68,9 @@ struct AttnArgs {
   // fused value decoder (kernel template flag): O_i = (L_g W_{P,i}) * Sigmoid(gate) for the heads of g
   const bf16 *wp, *gate;     // [n_h, d_l, d_h]; gate pre-activations [total, n_h*d_h] or NULL (gate off)
   bf16 *out; int hpq, dh, nh;   // [total, n_h*d_h]
+  // chunk mode (prefix != NULL): k, c are the caches [slot, max_seq, width]; the chunk's own rows are
+  // already in them behind the prefix[b] rows cached before (prefix[b] < 0: sequence skipped, zero output)
+  const int32_t *prefix, *slots; int max_seq;
 };
 
 // LDS of the fused value decoder: the normalised 256 x DLW tile (row operand) and the DLW x 256
@@ -114,15 +117,34 @@ __global__ __launch_bounds__(T::NT) void attn_prefill_kernel(AttnArgs a) {
   const int b = a.cu ? (rest % a.batch + lvl) % a.batch : rest % a.batch;
   const int g = (rest / a.batch) % a.nq, dlc = rest / (a.batch * a.nq);
   const int64_t start = a.cu ? a.cu[b] : (int64_t)b * a.per_seq;
-  const int Tb = a.cu ? a.cu[b + 1] - a.cu[b] : a.per_seq;
+  const int Tb = a.cu ? a.cu[b + 1] - a.cu[b] : a.per_seq;   // queries of this sequence
   const int q0 = qt * T::BQ;
   if (q0 >= Tb) return;
-  const int qw0 = q0 + wave * 32;                        // first query of this wave
-  const int kend = min(q0 + T::BQ, Tb);                  // keys [0, kend) are visible to this tile
+  const int P = a.prefix ? a.prefix[b] : 0;                  // keys cached before the first query
+  if (P < 0) {   // skipped sequence: zero rows
+    if constexpr (FUSE) {
+      const int64_t ldo = (int64_t)a.nh * a.dh;
+      bf16 *Ob = a.out + (start + q0) * ldo + g * a.hpq * a.dh;
+      for (int i = tid; i < T::BQ * 32; i += T::NT)
+        if (q0 + i / 32 < Tb) *reinterpret_cast<u32x4 *>(Ob + (int64_t)(i / 32) * ldo + (i % 32) * 8) = u32x4{0u, 0u, 0u, 0u};
+    } else {
+      bf16 *Lb = a.L + (start + q0) * (int64_t)(a.nq * a.dl) + g * a.dl + dlc * T::DLW;
+      for (int i = tid; i < T::BQ * (T::DLW / 8); i += T::NT)
+        if (q0 + i / (T::DLW / 8) < Tb)
+          *reinterpret_cast<u32x4 *>(Lb + (int64_t)(i / (T::DLW / 8)) * (a.nq * a.dl) + (i % (T::DLW / 8)) * 8) = u32x4{0u, 0u, 0u, 0u};
+    }
+    return;
+  }
+  const int Tk = P + Tb;                                     // keys of this sequence
+  const int qw0 = q0 + wave * 32;                            // first query of this wave
+  const int qa0 = P + qw0;                                   // its position among the keys
+  const int kend = P + min(q0 + T::BQ, Tb);                  // keys [0, kend) are visible to this tile
   const int ntiles = (kend + T::BK - 1) / T::BK;
-  const int kend_w = qw0 < Tb ? min(qw0 + 32, Tb) : 0;   // keys [0, kend_w) are visible to this wave
-  const char *Kb = reinterpret_cast<const char *>(a.k + start * a.wk_w + (g / a.qpk) * T::DH);
-  const char *Cb = reinterpret_cast<const char *>(a.c + start * a.wc_w + (g / a.qpc) * a.dl + dlc * T::DLW);
+  const int kend_w = qw0 < Tb ? P + min(qw0 + 32, Tb) : 0;   // keys [0, kend_w) are visible to this wave
+  int64_t krow0 = start;                                     // first key / latent row of the sequence
+  if (a.prefix) krow0 = (int64_t)(a.slots ? a.slots[b] : b) * a.max_seq;
+  const char *Kb = reinterpret_cast<const char *>(a.k + krow0 * a.wk_w + (g / a.qpk) * T::DH);
+  const char *Cb = reinterpret_cast<const char *>(a.c + krow0 * a.wc_w + (g / a.qpc) * a.dl + dlc * T::DLW);
   const unsigned wk2 = a.wk_w * 2, wc2 = a.wc_w * 2;
 
   // The wave's queries stay in registers for the whole kernel: the Q^T column operand of k-step ks is
@@ -150,13 +172,13 @@ __global__ __launch_bounds__(T::NT) void attn_prefill_kernel(AttnArgs a) {
   auto gload = [&](int t) {
     const int j0 = t * T::BK;
     if (k_loader) {
-      const unsigned r = min(j0 + k_row, Tb - 1);
+      const unsigned r = min(j0 + k_row, Tk - 1);
       rk = *reinterpret_cast<const u32x4 *>(Kb + (r * wk2 + k_ch * 16));
     }
     if (c_loader) {
 #pragma unroll
       for (int i = 0; i < T::C_LOADS; ++i) {
-        const unsigned r = min(j0 + c_row + i * T::C_RPP, Tb - 1);
+        const unsigned r = min(j0 + c_row + i * T::C_RPP, Tk - 1);
         rc[i] = *reinterpret_cast<const u32x4 *>(Cb + (r * wc2 + c_ch * 16));
       }
     }
@@ -184,7 +206,7 @@ __global__ __launch_bounds__(T::NT) void attn_prefill_kernel(AttnArgs a) {
   };
   // keys after the lane's query are masked in a block that touches the diagonal
   auto mask = [&](f32x16 &s, int jb) {
-    const int lim = qw0 + ln - jb;
+    const int lim = qa0 + ln - jb;
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       const int ko = 8 * (r >> 2) + 4 * h + (r & 3);
@@ -249,7 +271,7 @@ __global__ __launch_bounds__(T::NT) void attn_prefill_kernel(AttnArgs a) {
   if (nb_w > 0) {
     f32x16 s;
     scores(smem, s);
-    if (31 > qw0) mask(s, 0);
+    if (31 > qa0) mask(s, 0);
     softmax(s, pf, corr);
     corr = 1.f;   // the accumulators are still zero
   }
@@ -272,7 +294,7 @@ __global__ __launch_bounds__(T::NT) void attn_prefill_kernel(AttnArgs a) {
   // main part: blocks t and t+1 both lie entirely below this wave's diagonal
   int t = 0;
   if constexpr (T::PIPELINED) {
-  const int t_main = min(nb_w, qw0 >> 5) - 1;   // iterations 0 .. t_main-1
+  const int t_main = min(nb_w, qa0 >> 5) - 1;   // iterations 0 .. t_main-1
 #pragma unroll 1
   for (; t < t_main; ++t) {
     sstore(smem + fre);
@@ -349,7 +371,7 @@ __global__ __launch_bounds__(T::NT) void attn_prefill_kernel(AttnArgs a) {
       bf16x8 pn[2];
       if (t + 1 < nb_w) {
         scores(smem + nxt, s);
-        if ((t + 1) * 32 + 31 > qw0) mask(s, (t + 1) * 32);
+        if ((t + 1) * 32 + 31 > qa0) mask(s, (t + 1) * 32);
       } else {   // no further block: all-masked scores leave the statistics unchanged and give P = 0
 #pragma unroll
         for (int r = 0; r < 16; ++r) s[r] = -INFINITY;
@@ -536,6 +558,25 @@ void launch_attn_decoder_bf16(const Dims &d, const void *q, const void *k, const
   a.wp = (const bf16 *)wp; a.gate = d.gate ? (const bf16 *)gate : nullptr; a.out = (bf16 *)out;
   a.hpq = d.hpq; a.dh = d.dh; a.nh = d.nh;
   launch_attn<AttnNarrow, true>(a, d, batch, max_len, st);
+}
+
+void launch_attn_chunk_bf16(const Dims &d, const void *q, const gta_cache &cache, const int32_t *slots,
+                            const int32_t *prefix, const int32_t *cu, int batch, int64_t total, int max_chunk,
+                            void *L, const void *wp, const void *gate, void *out, bool fuse, hipStream_t st) {
+  AttnArgs a = attn_args(d, q, cache.k, cache.c, cu, batch, total);
+  a.prefix = prefix; a.slots = slots; a.max_seq = cache.max_seq;
+  a.L = (bf16 *)L;
+  if (fuse) {
+    a.wp = (const bf16 *)wp; a.gate = d.gate ? (const bf16 *)gate : nullptr; a.out = (bf16 *)out;
+    a.hpq = d.hpq; a.dh = d.dh; a.nh = d.nh;
+    launch_attn<AttnNarrow, true>(a, d, batch, max_chunk, st);
+  } else if (d.dh == 128) {
+    launch_attn<AttnWide, false>(a, d, batch, max_chunk, st);
+  } else if (d.dl % 128 == 0) {
+    launch_attn<AttnNarrow, false>(a, d, batch, max_chunk, st);
+  } else {
+    launch_attn<AttnSlim, false>(a, d, batch, max_chunk, st);
+  }
 }
 
 }  // namespace gta

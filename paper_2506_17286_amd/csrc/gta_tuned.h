@@ -10,6 +10,11 @@ bool tuned_decode_supported(const Dims &d);
 int tuned_prefill(const Dims &d, const gta_weights &w, const void *x, const int32_t *cu, int batch,
                   int64_t total, int max_len, const gta_cache *cache, const int32_t *slots, void *out,
                   const PrefillWs &ws, hipStream_t st);
+// chunked prefill: the chunk's tokens follow the rows the slots already hold (needs the MFMA attention kernel)
+bool tuned_prefill_chunk_supported(const Dims &d, int max_seq);
+int tuned_prefill_chunk(const Dims &d, const gta_weights &w, const void *x, const int32_t *cu, int batch,
+                        int64_t total, int max_chunk, const gta_cache &cache, const int32_t *slots, void *out,
+                        const PrefillWs &ws, hipStream_t st);
 int tuned_decode(const Dims &d, const gta_weights &w, const void *x_new, int batch, const gta_cache &cache,
                  const int32_t *slots, void *out, const DecodeWs &ws, hipStream_t st);
 
@@ -23,7 +28,8 @@ void tuned_decode_combine(const Dims &d, const float *part, const int32_t *oldle
 bool gemm_shapes_supported(const Dims &d);
 size_t proj_packed_bytes(const Dims &d);   // workspace for the packed [H, Wtot] weights, 0 if not used
 void launch_proj_gemm(const Dims &d, const gta_weights &w, const void *x, int M, const PrefillWs &ws,
-                      const gta_cache *cache, const int32_t *slots, int max_len, hipStream_t st);
+                      const gta_cache *cache, const int32_t *slots, int max_len, hipStream_t st,
+                      bool rope_by_token = false);
 void launch_decoder_gemm(const Dims &d, const void *L, const void *wp, const void *g, void *out, int M,
                          hipStream_t st);
 int skinny_ksplit(const Dims &d, int M);
@@ -40,5 +46,10 @@ bool attn_decoder_fusable(const Dims &d, int max_len);
 void launch_attn_decoder_bf16(const Dims &d, const void *q, const void *k, const void *c, const int32_t *cu,
                               int batch, int64_t total, int max_len, const void *wp, const void *gate, void *out,
                               hipStream_t st);
+// The same two against the caches: sequence b's keys / latents are rows 0 .. prefix[b] + T_b - 1 of its
+// slot, its queries sit at positions prefix[b] .. (prefix[b] < 0: zero rows).  L may be NULL when fused.
+void launch_attn_chunk_bf16(const Dims &d, const void *q, const gta_cache &cache, const int32_t *slots,
+                            const int32_t *prefix, const int32_t *cu, int batch, int64_t total, int max_chunk,
+                            void *L, const void *wp, const void *gate, void *out, bool fuse, hipStream_t st);
 
 }  // namespace gta

@@ -27,4 +27,25 @@ int tuned_prefill(const Dims &d, const gta_weights &w, const void *x, const int3
   return check_launch();
 }
 
+bool tuned_prefill_chunk_supported(const Dims &d, int max_seq) {
+  return tuned_prefill_supported(d) && attn_prefill_supported(d, max_seq);
+}
+
+// Chunked prefill: App. B.1.3 for several new tokens per sequence.  The projection stores the chunk's
+// key / latent rows behind the cached ones; attention then reads keys and latents from the caches.
+int tuned_prefill_chunk(const Dims &d, const gta_weights &w, const void *x, const int32_t *cu, int batch,
+                        int64_t total, int max_chunk, const gta_cache &cache, const int32_t *slots, void *out,
+                        const PrefillWs &ws, hipStream_t st) {
+  const int M = (int)total;
+  launch_prefill_chunk_setup(d, cu, batch, total, ws.seq_id, ws.pos, ws.rope, ws.prefix, cache, slots, st);
+  launch_proj_gemm(d, w, x, M, ws, &cache, slots, max_chunk, st, true);
+  void *heads = w.wo ? ws.o : out;
+  const bool fuse = attn_decoder_fusable(d, cache.max_seq);
+  launch_attn_chunk_bf16(d, ws.q, cache, slots, ws.prefix, cu, batch, total, max_chunk, ws.l, w.wp, ws.g, heads, fuse, st);
+  if (!fuse) launch_decoder_gemm(d, ws.l, w.wp, ws.g, heads, M, st);
+  if (w.wo) launch_plain_gemm(ws.o, d.wg_w, M, d.H, d.wg_w, w.wo, out, st);
+  launch_prefill_chunk_commit(cache, slots, cu, batch, total, ws.prefix, st);
+  return check_launch();
+}
+
 }  // namespace gta

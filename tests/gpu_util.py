@@ -104,3 +104,22 @@ def run_decode(wl, wdev, x_np, cache: DeviceCache, slots=None, num_splits=0, gat
     B.gta_decode(cfg, B.make_weights(wdev), x, batch, cache.struct, sl, out, num_splits, ws)
     torch.cuda.synchronize()
     return out
+
+
+def run_prefill_chunk(wl, wdev, x_np, cu_np, cache: DeviceCache, slots=None, gate=True):
+    """gta_prefill_chunk through the C ABI: the chunks follow whatever the slots already hold."""
+    cfg = B.config_of(wl)
+    if not gate:
+        cfg.gate = B.GTA_GATE_OFF
+    total = x_np.shape[0]
+    x = B.to_device(x_np, wl.dtype)
+    cu = torch.from_numpy(np.asarray(cu_np, dtype=np.int32)).cuda()
+    batch = len(cu_np) - 1
+    max_chunk = int(np.diff(cu_np).max())
+    width = wl.d_model if wdev.get("wo") is not None else wl.n_heads * wl.head_dim
+    out = torch.full((total, width), float("nan"), dtype=x.dtype, device="cuda")
+    ws = B.alloc_workspace(B.gta_workspace_bytes(cfg, B.GTA_MODE_PREFILL_CHUNK, batch, total, max_chunk))
+    sl = None if slots is None else torch.from_numpy(np.asarray(slots, dtype=np.int32)).cuda()
+    B.gta_prefill_chunk(cfg, B.make_weights(wdev), x, cu, batch, total, max_chunk, cache.struct, sl, out, ws)
+    torch.cuda.synchronize()
+    return out

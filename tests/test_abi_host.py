@@ -88,6 +88,12 @@ def test_null_and_misaligned_arguments_are_rejected_on_the_host():
     cache = B.gta_cache(fake, fake, fake, fake, 2, 64)
     rc = lib.gta_prefill(ctypes.byref(cfg), ctypes.byref(w), fake, None, 1, 128, 128, ctypes.byref(cache), None, fake, fake, 1 << 30, None)
     assert rc == B.GTA_ERR_SHAPE                       # sequence longer than the cache rows
+    rc = lib.gta_prefill_chunk(ctypes.byref(cfg), ctypes.byref(w), fake, None, 1, 16, 16, None, None, fake, fake, 1 << 30, None)
+    assert rc == B.GTA_ERR_NULL                        # chunked prefill needs a cache
+    rc = lib.gta_prefill_chunk(ctypes.byref(cfg), ctypes.byref(w), fake, None, 1, 128, 128, ctypes.byref(cache), None, fake, fake, 1 << 30, None)
+    assert rc == B.GTA_ERR_SHAPE                       # chunk longer than the cache rows
+    rc = lib.gta_prefill_chunk(ctypes.byref(cfg), ctypes.byref(w), fake, None, 1, 16, 16, ctypes.byref(cache), None, fake, fake, 1 << 30, None)
+    assert rc == B.GTA_ERR_UNSUPPORTED                 # fp32: no MFMA attention kernel for this configuration
     rc = lib.gta_decode(ctypes.byref(cfg), ctypes.byref(w), fake, 1, None, None, fake, 0, fake, 1 << 30, None)
     assert rc == B.GTA_ERR_NULL
     rc = lib.gta_decode(ctypes.byref(cfg), ctypes.byref(w), fake, 3, ctypes.byref(cache), None, fake, 0, fake, 1 << 30, None)

@@ -1,0 +1,118 @@
+"""GPU parity of chunked prefill (a chunk of new tokens behind the rows a slot already holds):
+splitting sequences into a prefix and a chunk, or into several chunks, must give the rows of ONE causal
+pass over the whole sequences, which is what the oracle computes."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import gta_oracle as orc
+from paper_2506_17286_amd import binding as B
+from paper_2506_17286_amd import workloads as W
+
+import gpu_util as U
+
+pytestmark = pytest.mark.gpu
+
+
+def _base(shape):
+    if shape == "paper":
+        return W.PAPER_WORKLOADS[0]
+    return W.WORKLOADS[1] if shape == "1b" else W.WORKLOADS[4]
+
+
+def _inputs(wl, lens, with_wo=False):
+    rng = W.make_rng(wl)
+    w = W.draw_weights(wl, rng, with_wo=with_wo)
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    x = W.draw_hidden(wl, rng, int(cu[-1]))
+    return w, cu, x
+
+
+@pytest.mark.parametrize("shape,with_wo", [("1b", False), ("paper", False), ("paper", True), ("wide", False)])
+def test_prefix_then_chunk_equals_one_pass(shape, with_wo):
+    """Sequences cut into (prefix, chunk) at points inside and on tile borders, one of them with an empty
+    prefix: prefill the prefixes, then the chunks; outputs of the chunk rows, every cached row and the
+    lengths against one oracle pass over the whole sequences."""
+    lens = [300, 129, 64, 37, 513]
+    pre = [37, 0, 63, 36, 256]
+    slots = [4, 0, 5, 2, 1]
+    wl = W.scaled(_base(shape), batch=len(lens), seqlen=max(lens), min_seqlen=None)
+    w, cu, x = _inputs(wl, lens, with_wo)
+    wdev = U.upload_weights(w, wl.dtype)
+    cache = U.DeviceCache(wl, 6, 520, fill=-3.0)
+    # prefixes of the sequences that have one
+    has = [b for b in range(len(lens)) if pre[b] > 0]
+    xp = np.concatenate([x[cu[b]:cu[b] + pre[b]] for b in has])
+    cup = np.concatenate([[0], np.cumsum([pre[b] for b in has])]).astype(np.int32)
+    U.run_prefill(wl, wdev, xp, cup, cache=cache, slots=[slots[b] for b in has])
+    # the chunks of all sequences
+    xc = np.concatenate([x[cu[b] + pre[b]:cu[b + 1]] for b in range(len(lens))])
+    cuc = np.concatenate([[0], np.cumsum([lens[b] - pre[b] for b in range(len(lens))])]).astype(np.int32)
+    out = U.run_prefill_chunk(wl, wdev, xc, cuc, cache, slots=slots)
+    ref, Kref, Cref = orc.prefill(U.oracle_config(wl), U.oracle_weights(w), x, cu)
+    ref_rows = np.concatenate([ref[cu[b] + pre[b]:cu[b + 1]] for b in range(len(lens))])
+    U.assert_close(U.f64(out), ref_rows, wl.dtype, f"chunked prefill {shape}")
+    kc, cc = U.f64(cache.k), U.f64(cache.c)
+    for b, s in enumerate(slots):
+        U.assert_close(kc[s, :lens[b]], Kref[cu[b]:cu[b + 1]], wl.dtype, "K cache")
+        U.assert_close(cc[s, :lens[b]], Cref[cu[b]:cu[b + 1]], wl.dtype, "C cache")
+        assert np.all(kc[s, lens[b]:] == -3.0) and np.all(cc[s, lens[b]:] == -3.0)
+        assert int(cache.seq_lens[s]) == lens[b]
+    assert np.all(kc[3] == -3.0) and int(cache.seq_lens[3]) == 0
+    assert np.all(cache.status.cpu().numpy() == 0)
+
+
+@pytest.mark.parametrize("shape", ["1b", "paper"])
+def test_several_chunks_in_a_row(shape):
+    """One sequence of 700 tokens fed as chunks of 100, 344 and 256 next to a short one fed as 1, 1, 30."""
+    lens = [700, 32]
+    parts = [[100, 344, 256], [1, 1, 30]]
+    wl = W.scaled(_base(shape), batch=2, seqlen=700, min_seqlen=None)
+    w, cu, x = _inputs(wl, lens)
+    wdev = U.upload_weights(w, wl.dtype)
+    cache = U.DeviceCache(wl, 2, 704)
+    ref, Kref, Cref = orc.prefill(U.oracle_config(wl), U.oracle_weights(w), x, cu)
+    done = [0, 0]
+    for step in range(3):
+        n = [parts[b][step] for b in range(2)]
+        xc = np.concatenate([x[cu[b] + done[b]:cu[b] + done[b] + n[b]] for b in range(2)])
+        cuc = np.concatenate([[0], np.cumsum(n)]).astype(np.int32)
+        out = U.run_prefill_chunk(wl, wdev, xc, cuc, cache)
+        ref_rows = np.concatenate([ref[cu[b] + done[b]:cu[b] + done[b] + n[b]] for b in range(2)])
+        U.assert_close(U.f64(out), ref_rows, wl.dtype, f"chunk {step}")
+        done = [done[b] + n[b] for b in range(2)]
+        assert cache.seq_lens.cpu().tolist() == done
+    U.assert_close(U.f64(cache.k)[0, :700], Kref[:700], wl.dtype, "K cache")
+    U.assert_close(U.f64(cache.c)[1, :32], Cref[700:], wl.dtype, "C cache")
+
+
+def test_chunk_that_does_not_fit_is_skipped():
+    """A chunk that would overflow its slot stores nothing, returns zero rows and flags the slot; the
+    other sequence of the call is unaffected."""
+    lens = [60, 40]
+    wl = W.scaled(W.PAPER_WORKLOADS[0], batch=2, seqlen=60, min_seqlen=None)
+    w, cu, x = _inputs(wl, lens)
+    wdev = U.upload_weights(w, wl.dtype)
+    cache = U.DeviceCache(wl, 2, 64, fill=-3.0)
+    cache.seq_lens[0] = 10          # 10 + 60 > 64: does not fit (the 10 rows are never read)
+    out = U.run_prefill_chunk(wl, wdev, x, cu, cache)
+    ref, Kref, Cref = orc.prefill(U.oracle_config(wl), U.oracle_weights(w), x[60:], np.array([0, 40], dtype=np.int32))
+    got = U.f64(out)
+    assert np.all(got[:60] == 0.0)
+    U.assert_close(got[60:], ref, wl.dtype, "sequence that fits")
+    assert cache.seq_lens.cpu().tolist() == [10, 40]
+    assert cache.status.cpu().tolist() == [B.GTA_ERR_CACHE_FULL, 0]
+    assert np.all(U.f64(cache.k)[0] == -3.0) and np.all(U.f64(cache.c)[0] == -3.0)
+
+
+def test_chunked_prefill_is_refused_without_the_mfma_kernels():
+    wl = W.WORKLOADS[0]   # fp32: shape-generic path only
+    cfg = B.config_of(wl)
+    w = W.draw_weights(wl, W.make_rng(wl))
+    wdev = U.upload_weights(w, wl.dtype)
+    cache = U.DeviceCache(wl, 1, 128)
+    x = torch.zeros((8, wl.d_model), dtype=torch.float32, device="cuda")
+    out = torch.zeros((8, wl.n_heads * wl.head_dim), dtype=torch.float32, device="cuda")
+    ws = B.alloc_workspace(1 << 20)
+    rc = B.gta_prefill_chunk(cfg, B.make_weights(wdev), x, None, 1, 8, 8, cache.struct, None, out, ws, check=False)
+    assert rc == B.GTA_ERR_UNSUPPORTED
