@@ -35,6 +35,20 @@ def _rope_vec(v, pos, base):
     return out
 
 
+def _gate(kind, z):
+    """Gate factor from the pre-activation: Sigmoid (Sec. 3.2), or Silu / ReLU^2 (ablation on the choice
+    of nonlinearity), or 1 when the gate is switched off."""
+    if kind is True or kind == "sigmoid":
+        return 1.0 / (1.0 + math.exp(-z))
+    if kind == "silu":
+        return z / (1.0 + math.exp(-z))
+    if kind == "relu2":
+        return max(z, 0.0) ** 2
+    if kind is False or kind == "off":
+        return 1.0
+    raise ValueError(kind)
+
+
 def brute_force_sequence(x, wq, wk, wc, wg, wp, *, n_heads, n_qgroups, n_kgroups, n_cgroups,
                          head_dim, latent_dim, rope=False, rope_base=10000.0, gate=True,
                          wo=None):
@@ -61,10 +75,7 @@ def brute_force_sequence(x, wq, wk, wc, wg, wp, *, n_heads, n_qgroups, n_kgroups
         # linear part of the decoder, C W_P, per key row
         cp = [[sum(c[j][a] * wp[i][a][e] for a in range(dl)) for e in range(dh)] for j in range(T)]
         for t in range(T):
-            if gate:
-                gt = [1.0 / (1.0 + math.exp(-_dot_col(x[t], wg, i * dh + e))) for e in range(dh)]
-            else:
-                gt = [1.0] * dh
+            gt = [_gate(gate, _dot_col(x[t], wg, i * dh + e)) for e in range(dh)]
             s = [sum(q[t][e] * k[j][e] for e in range(dh)) / math.sqrt(dh) for j in range(t + 1)]
             m = max(s)
             p = [math.exp(v - m) for v in s]

@@ -58,7 +58,9 @@ class OracleConfig:
     latent_dim: int       # d_l
     rope: bool = False
     rope_base: float = 10000.0
-    gate: bool = True     # False => gate factor 1 (degenerate-case tests only)
+    # gate nonlinearity: True / "sigmoid" (Sec. 3.2), "silu", "relu2" (the other two of the ablation on
+    # the choice of nonlinearity), False / "off" => factor 1 (degenerate-case tests only)
+    gate: object = True
     softmax_scale: Optional[float] = None  # None => 1/sqrt(d_h)
 
     def check(self) -> None:
@@ -103,6 +105,21 @@ def sigmoid(z: np.ndarray) -> np.ndarray:
     z = np.asarray(z, dtype=np.float64)
     e = np.exp(-np.abs(z))
     return np.where(z >= 0, 1.0 / (1.0 + e), e / (1.0 + e))
+
+
+def gate_factor(kind, z: np.ndarray) -> np.ndarray:
+    """The factor the decoded value is multiplied by, from the gate pre-activation z = x_t W_{G,i}:
+    Sigmoid(z) in the method (Sec. 3.2); the ablation on the choice of nonlinearity also trains Silu,
+    z * Sigmoid(z), and ReLU^2, max(z, 0)^2."""
+    if kind is True or kind == "sigmoid":
+        return sigmoid(z)
+    if kind == "silu":
+        return np.asarray(z, dtype=np.float64) * sigmoid(z)
+    if kind == "relu2":
+        return np.square(np.maximum(np.asarray(z, dtype=np.float64), 0.0))
+    if kind is False or kind == "off":
+        return np.ones_like(np.asarray(z, dtype=np.float64))
+    raise ValueError(f"unknown gate {kind!r}")
 
 
 def rope_rotate(v: np.ndarray, positions: np.ndarray, base: float) -> np.ndarray:
@@ -169,7 +186,7 @@ def decode_heads(cfg: OracleConfig, w: OracleWeights, L: np.ndarray, G: np.ndarr
     O = np.empty((R, cfg.n_heads, cfg.head_dim), dtype=np.float64)
     for i in range(cfg.n_heads):
         z = L[:, cfg.q_of_head(i), :] @ w.wp[i]
-        O[:, i, :] = z * sigmoid(G[:, i, :]) if cfg.gate else z
+        O[:, i, :] = z * gate_factor(cfg.gate, G[:, i, :])
     O = O.reshape(R, cfg.n_heads * cfg.head_dim)
     if w.wo is not None:
         O = O @ w.wo

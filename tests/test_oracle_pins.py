@@ -159,6 +159,34 @@ def test_zero_gate_weights_give_one_half():
     assert np.abs(on - off).max() > 1e-3                                     # the gate does act
 
 
+@pytest.mark.parametrize("kind", ["silu", "relu2"])
+def test_other_gate_nonlinearities(kind):
+    """The ablation's Silu and ReLU^2 gates: against the brute-force per-head loops, against torch's own
+    functions on the gate pre-activations (the gated output is the ungated one times the factor, row by
+    row), and the closed forms silu(0) = relu(0)^2 = 0 for zero gate weights."""
+    rng = np.random.default_rng(16)
+    cfg = orc.OracleConfig(d_model=5, n_heads=4, n_qgroups=2, n_kgroups=1, n_cgroups=2, head_dim=4, latent_dim=6,
+                           rope=True, rope_base=50.0, gate=kind)
+    w = _weights(rng, cfg)
+    x = rng.standard_normal((7, cfg.d_model))
+    got, _, _ = orc.prefill_sequence(cfg, w, x)
+    ref = brute_force_sequence(
+        x.tolist(), w.wq.tolist(), w.wk.tolist(), w.wc.tolist(), w.wg.tolist(), w.wp.tolist(),
+        n_heads=4, n_qgroups=2, n_kgroups=1, n_cgroups=2, head_dim=4, latent_dim=6, rope=True, rope_base=50.0, gate=kind)
+    np.testing.assert_allclose(got, np.array(ref), rtol=0, atol=1e-12)
+    off, _, _ = orc.prefill_sequence(orc.OracleConfig(**{**cfg.__dict__, "gate": False}), w, x)
+    z = torch.from_numpy(x @ w.wg)
+    fac = torch.nn.functional.silu(z) if kind == "silu" else torch.relu(z) ** 2
+    np.testing.assert_allclose(got, off * fac.numpy(), rtol=0, atol=1e-13)
+    w0 = orc.OracleWeights(w.wq, w.wk, w.wc, np.zeros_like(w.wg), w.wp)
+    zero, _, _ = orc.prefill_sequence(cfg, w0, x)
+    assert np.all(zero == 0.0)
+    dec = orc.OracleConfig(**{**cfg.__dict__, "gate": "sigmoid"})
+    sig, _, _ = orc.prefill_sequence(dec, w, x)
+    on, _, _ = orc.prefill_sequence(orc.OracleConfig(**{**cfg.__dict__, "gate": True}), w, x)
+    assert np.array_equal(sig, on) and np.abs(got - sig).max() > 1e-3
+
+
 def test_single_token():
     rng = np.random.default_rng(7)
     cfg = _cfg(rope=True)
