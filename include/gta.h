@@ -49,7 +49,7 @@ typedef enum {
 } gta_status;
 
 enum { GTA_F32 = 0, GTA_BF16 = 1 };            /* gta_config.dtype */
-enum { GTA_GATE_SIGMOID = 0, GTA_GATE_OFF = 1 }; /* gta_config.gate  */
+enum { GTA_GATE_SIGMOID = 0, GTA_GATE_OFF = 1, GTA_GATE_SILU = 2, GTA_GATE_RELU2 = 3 }; /* gta_config.gate  */
 enum { GTA_MODE_PREFILL = 0, GTA_MODE_DECODE = 1, GTA_MODE_PREFILL_CHUNK = 2 };
 
 /* Hyper-parameters of one GTA layer (Sec. 3.2).  Host memory. */
@@ -67,7 +67,9 @@ typedef struct {
                             (j, j + d_h/2) turns by pos * rope_base^(-2j/d_h); the latent value is
                             never rotated.  Positions count from 0 within each sequence. */
   float   rope_base;     /* e.g. 10000 */
-  int32_t gate;          /* GTA_GATE_SIGMOID (Sec. 3.2) | GTA_GATE_OFF (factor 1; for tests) */
+  int32_t gate;          /* GTA_GATE_SIGMOID (Sec. 3.2) | GTA_GATE_SILU, GTA_GATE_RELU2 (the other two
+                            nonlinearities of the ablation: z*Sigmoid(z), max(z,0)^2) | GTA_GATE_OFF
+                            (factor 1; for tests) */
   float   softmax_scale; /* 0 => 1/sqrt(d_h) (Sec. 3.3) */
 } gta_config;
 

@@ -14,7 +14,9 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libgta.so")
 
 GTA_F32, GTA_BF16 = 0, 1
-GTA_GATE_SIGMOID, GTA_GATE_OFF = 0, 1
+GTA_GATE_SIGMOID, GTA_GATE_OFF, GTA_GATE_SILU, GTA_GATE_RELU2 = 0, 1, 2, 3
+GATE_CODES = {True: GTA_GATE_SIGMOID, "sigmoid": GTA_GATE_SIGMOID, False: GTA_GATE_OFF, "off": GTA_GATE_OFF,
+              "silu": GTA_GATE_SILU, "relu2": GTA_GATE_RELU2}
 GTA_MODE_PREFILL, GTA_MODE_DECODE, GTA_MODE_PREFILL_CHUNK = 0, 1, 2
 GTA_OK = 0
 GTA_ERR_NULL, GTA_ERR_SHAPE, GTA_ERR_ALIGN, GTA_ERR_DTYPE = -1, -2, -3, -4
@@ -105,7 +107,7 @@ def make_config(*, d_model, n_heads, n_qgroups, n_kgroups, n_cgroups, head_dim, 
                 rope=False, rope_base=10000.0, gate=True, softmax_scale=0.0) -> gta_config:
     dt = {"f32": GTA_F32, "bf16": GTA_BF16}.get(dtype, dtype)
     return gta_config(d_model, n_heads, n_qgroups, n_kgroups, n_cgroups, head_dim, latent_dim, dt,
-                      int(bool(rope)), float(rope_base), GTA_GATE_SIGMOID if gate else GTA_GATE_OFF,
+                      int(bool(rope)), float(rope_base), GATE_CODES[gate],
                       float(softmax_scale))
 
 

@@ -10,7 +10,8 @@ namespace gta {
 static int make_dims(const gta_config *c, Dims *out) {
   if (!c) return GTA_ERR_NULL;
   if (c->dtype != GTA_F32 && c->dtype != GTA_BF16) return GTA_ERR_DTYPE;
-  if (c->gate != GTA_GATE_SIGMOID && c->gate != GTA_GATE_OFF) return GTA_ERR_DTYPE;
+  if (c->gate != GTA_GATE_SIGMOID && c->gate != GTA_GATE_OFF && c->gate != GTA_GATE_SILU && c->gate != GTA_GATE_RELU2)
+    return GTA_ERR_DTYPE;
   if (c->rope != 0 && c->rope != 1) return GTA_ERR_DTYPE;
   if (c->d_model <= 0 || c->n_heads <= 0 || c->n_qgroups <= 0 || c->n_kgroups <= 0 || c->n_cgroups <= 0 ||
       c->head_dim <= 0 || c->latent_dim <= 0)
@@ -29,7 +30,8 @@ static int make_dims(const gta_config *c, Dims *out) {
   d.hpq = d.nh / d.nq; d.qpk = d.nq / d.nk; d.qpc = d.nq / d.nc;
   d.wq_w = d.nq * d.dh; d.wk_w = d.nk * d.dh; d.wc_w = d.nc * d.dl; d.wg_w = d.nh * d.dh;
   d.wtot = (int)wtot;
-  d.dtype = c->dtype; d.rope = c->rope; d.gate = c->gate == GTA_GATE_SIGMOID ? 1 : 0;
+  d.dtype = c->dtype; d.rope = c->rope; d.gate = c->gate == GTA_GATE_SIGMOID ? kGateSigmoid : c->gate == GTA_GATE_SILU ? kGateSilu :
+           c->gate == GTA_GATE_RELU2 ? kGateRelu2 : kGateOff;
   d.scale = c->softmax_scale > 0.f ? c->softmax_scale : (float)(1.0 / sqrt((double)c->head_dim));
   d.rope_base = (double)c->rope_base;
   *out = d;

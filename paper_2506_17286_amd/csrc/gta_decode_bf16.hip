@@ -824,7 +824,8 @@ __global__ __launch_bounds__(512) void decode_tail_kernel(Dims d, const float *_
 #pragma unroll
     for (int q = 0; q < 8; ++q) v += red[(q * ROWS + r) * d.dh + ee];
     const int col = head * d.dh + ee;
-    if (d.gate) v *= 1.0f / (1.0f + __expf(-gz[o]));
+    if (d.gate == kGateSigmoid) v *= 1.0f / (1.0f + __expf(-gz[o]));
+    else if (d.gate) v *= gate_factor(d.gate, gz[o]);
     out[(int64_t)b * d.wg_w + col] = (TO)v;
   }
 }
@@ -944,7 +945,8 @@ __global__ __launch_bounds__(512) void decode_tail1_kernel(Dims d, const float *
     float o = 0.f;
 #pragma unroll
     for (int q = 0; q < 8; ++q) o += redz[q][tid];
-    if (d.gate) o *= 1.0f / (1.0f + __expf(-gz));
+    if (d.gate == kGateSigmoid) o *= 1.0f / (1.0f + __expf(-gz));
+    else if (d.gate) o *= gate_factor(d.gate, gz);
     out[(int64_t)b * d.wg_w + head * DH + tid] = live ? (TO)o : (TO)0.f;
   }
 }

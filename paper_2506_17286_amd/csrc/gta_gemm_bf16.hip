@@ -15,6 +15,8 @@
 // LDS staging with two LDS stages (one barrier per k-tile).
 #include <math.h>
 
+#include <type_traits>
+
 #include "gta_tuned.h"
 
 namespace gta {
@@ -618,7 +620,8 @@ __global__ __launch_bounds__(T::NT) void decoder_gemm_kernel(DecoderArgs a) {
         if (a.gate) {
           const bf16x4 gz = *reinterpret_cast<const bf16x4 *>(a.g + o);
 #pragma unroll
-          for (int i = 0; i < 4; ++i) v[i] *= 1.0f / (1.0f + __expf(-(float)gz[i]));
+          for (int i = 0; i < 4; ++i)
+            v[i] *= a.gate == kGateSigmoid ? 1.0f / (1.0f + __expf(-(float)gz[i])) : gate_factor(a.gate, (float)gz[i]);
         }
         *reinterpret_cast<bf16x4 *>(a.out + o) = pack4(v[0], v[1], v[2], v[3]);
       }
@@ -683,28 +686,35 @@ __global__ __launch_bounds__(T::NT) void decoder_pair_kernel(DecoderArgs a) {
     __syncthreads();
   }
   // one row block (tm) at a time: all 16 gate reads of the block are issued before the first is used
-#pragma unroll
-  for (int tm = 0; tm < T::TM; ++tm) {
-    bf16x4 gz[T::TN][4];
-    if constexpr (GATE) {
-#pragma unroll
-      for (int tn = 0; tn < T::TN; ++tn)
-#pragma unroll
-        for (int rq = 0; rq < 4; ++rq) gz[tn][rq] = *reinterpret_cast<const bf16x4 *>(smem + out_lds_offset<T>(tm, tn, rq));
-    }
-#pragma unroll
-    for (int tn = 0; tn < T::TN; ++tn)
-#pragma unroll
-      for (int rq = 0; rq < 4; ++rq) {
-        float v[4] = {acc[tn][tm][rq * 4], acc[tn][tm][rq * 4 + 1], acc[tn][tm][rq * 4 + 2], acc[tn][tm][rq * 4 + 3]};
-        if constexpr (GATE) {
-#pragma unroll
-          for (int i = 0; i < 4; ++i)
-            v[i] *= __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * (float)gz[tn][rq][i]));
-        }
-        *reinterpret_cast<bf16x4 *>(smem + out_lds_offset<T>(tm, tn, rq)) = pack4(v[0], v[1], v[2], v[3]);
+  // the Sigmoid of the method takes the short path; the other nonlinearities a general one
+  auto gate_rows = [&](auto sig_tag) {
+    constexpr bool SIG = decltype(sig_tag)::value;
+  #pragma unroll
+    for (int tm = 0; tm < T::TM; ++tm) {
+      bf16x4 gz[T::TN][4];
+      if constexpr (GATE) {
+  #pragma unroll
+        for (int tn = 0; tn < T::TN; ++tn)
+  #pragma unroll
+          for (int rq = 0; rq < 4; ++rq) gz[tn][rq] = *reinterpret_cast<const bf16x4 *>(smem + out_lds_offset<T>(tm, tn, rq));
       }
-  }
+  #pragma unroll
+      for (int tn = 0; tn < T::TN; ++tn)
+  #pragma unroll
+        for (int rq = 0; rq < 4; ++rq) {
+          float v[4] = {acc[tn][tm][rq * 4], acc[tn][tm][rq * 4 + 1], acc[tn][tm][rq * 4 + 2], acc[tn][tm][rq * 4 + 3]};
+          if constexpr (GATE) {
+  #pragma unroll
+            for (int i = 0; i < 4; ++i)
+              v[i] *= SIG ? __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * (float)gz[tn][rq][i]))
+                          : gate_factor(a.gate, (float)gz[tn][rq][i]);
+          }
+          *reinterpret_cast<bf16x4 *>(smem + out_lds_offset<T>(tm, tn, rq)) = pack4(v[0], v[1], v[2], v[3]);
+        }
+    }
+  };
+  if (!GATE || a.gate == kGateSigmoid) gate_rows(std::true_type{});
+  else gate_rows(std::false_type{});
   __syncthreads();
   for_each_out_chunk(smem, [&](int r, int ch, u32x4 v) {
     if (m0 + r < a.M) *reinterpret_cast<u32x4 *>(a.out + (int64_t)(m0 + r) * ldo + col0 + ch * 8) = v;
@@ -745,28 +755,35 @@ __global__ __launch_bounds__(T::NT) void decoder_multi_kernel(DecoderArgs a) {
     for (int it = 0; it < 32; ++it) *reinterpret_cast<u32x4 *>(smem + (it * 8 + r0) * kOutPitch + ch * 16) = gt[it];
     __syncthreads();
   }
-#pragma unroll
-  for (int tm = 0; tm < T::TM; ++tm) {
-    bf16x4 gz[T::TN][4];
-    if constexpr (GATE) {
-#pragma unroll
-      for (int tn = 0; tn < T::TN; ++tn)
-#pragma unroll
-        for (int rq = 0; rq < 4; ++rq) gz[tn][rq] = *reinterpret_cast<const bf16x4 *>(smem + out_lds_offset<T>(tm, tn, rq));
-    }
-#pragma unroll
-    for (int tn = 0; tn < T::TN; ++tn)
-#pragma unroll
-      for (int rq = 0; rq < 4; ++rq) {
-        float v[4] = {acc[tn][tm][rq * 4], acc[tn][tm][rq * 4 + 1], acc[tn][tm][rq * 4 + 2], acc[tn][tm][rq * 4 + 3]};
-        if constexpr (GATE) {
-#pragma unroll
-          for (int i = 0; i < 4; ++i)
-            v[i] *= __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * (float)gz[tn][rq][i]));
-        }
-        *reinterpret_cast<bf16x4 *>(smem + out_lds_offset<T>(tm, tn, rq)) = pack4(v[0], v[1], v[2], v[3]);
+  // the Sigmoid of the method takes the short path; the other nonlinearities a general one
+  auto gate_rows = [&](auto sig_tag) {
+    constexpr bool SIG = decltype(sig_tag)::value;
+  #pragma unroll
+    for (int tm = 0; tm < T::TM; ++tm) {
+      bf16x4 gz[T::TN][4];
+      if constexpr (GATE) {
+  #pragma unroll
+        for (int tn = 0; tn < T::TN; ++tn)
+  #pragma unroll
+          for (int rq = 0; rq < 4; ++rq) gz[tn][rq] = *reinterpret_cast<const bf16x4 *>(smem + out_lds_offset<T>(tm, tn, rq));
       }
-  }
+  #pragma unroll
+      for (int tn = 0; tn < T::TN; ++tn)
+  #pragma unroll
+        for (int rq = 0; rq < 4; ++rq) {
+          float v[4] = {acc[tn][tm][rq * 4], acc[tn][tm][rq * 4 + 1], acc[tn][tm][rq * 4 + 2], acc[tn][tm][rq * 4 + 3]};
+          if constexpr (GATE) {
+  #pragma unroll
+            for (int i = 0; i < 4; ++i)
+              v[i] *= SIG ? __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * (float)gz[tn][rq][i]))
+                          : gate_factor(a.gate, (float)gz[tn][rq][i]);
+          }
+          *reinterpret_cast<bf16x4 *>(smem + out_lds_offset<T>(tm, tn, rq)) = pack4(v[0], v[1], v[2], v[3]);
+        }
+    }
+  };
+  if (!GATE || a.gate == kGateSigmoid) gate_rows(std::true_type{});
+  else gate_rows(std::false_type{});
   __syncthreads();
   for_each_out_chunk(smem, [&](int r, int ch, u32x4 v) {
     if (m0 + r < a.M) *reinterpret_cast<u32x4 *>(a.out + (int64_t)(m0 + r) * ldo + col0 + ch * 8) = v;

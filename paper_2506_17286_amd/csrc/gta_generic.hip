@@ -84,7 +84,8 @@ template <typename TO> struct EpiGate {
   TO *out; int64_t ldo; const float *g; int64_t ldg; int dh; int gate;
   __device__ void operator()(int row, int col, int z, float v) const {
     int c = z * dh + col;
-    if (gate) v *= sigmoid_f32(g[(int64_t)row * ldg + c]);
+    if (gate == kGateSigmoid) v *= sigmoid_f32(g[(int64_t)row * ldg + c]);
+    else if (gate) v *= gate_factor(gate, g[(int64_t)row * ldg + c]);
     stf(out, (int64_t)row * ldo + c, v);
   }
 };

@@ -21,11 +21,21 @@ struct Dims {
   int wtot;         // wq_w + wk_w + wc_w + wg_w
   int dtype;        // GTA_F32 | GTA_BF16
   int rope;         // 0 | 1
-  int gate;         // 1 = sigmoid, 0 = off
+  int gate;         // kGateOff | kGateSigmoid | kGateSilu | kGateRelu2
   float scale;      // softmax scale
   double rope_base;
   int esize() const { return dtype == GTA_BF16 ? 2 : 4; }
 };
+
+enum { kGateOff = 0, kGateSigmoid = 1, kGateSilu = 2, kGateRelu2 = 3 };
+
+// Factor the decoded value is multiplied by, from the gate pre-activation z: Sigmoid(z) (Sec. 3.2), or
+// one of the ablation's other nonlinearities, z * Sigmoid(z) and max(z, 0)^2.  kind != kGateOff.
+__device__ __forceinline__ float gate_factor(int kind, float z) {
+  const float s = __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * z));
+  const float r = fmaxf(z, 0.f);
+  return kind == kGateSigmoid ? s : (kind == kGateSilu ? z * s : r * r);
+}
 
 static inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 

@@ -68,6 +68,7 @@ struct AttnArgs {
   // fused value decoder (kernel template flag): O_i = (L_g W_{P,i}) * Sigmoid(gate) for the heads of g
   const bf16 *wp, *gate;     // [n_h, d_l, d_h]; gate pre-activations [total, n_h*d_h] or NULL (gate off)
   bf16 *out; int hpq, dh, nh;   // [total, n_h*d_h]
+  int gate_kind;                // nonlinearity of the gate (kGateSigmoid, ..)
   // chunk mode (prefix != NULL): k, c are the caches [slot, max_seq, width]; the chunk's own rows are
   // already in them behind the prefix[b] rows cached before (prefix[b] < 0: sequence skipped, zero output)
   const int32_t *prefix, *slots; int max_seq;
@@ -466,8 +467,7 @@ __global__ __launch_bounds__(T::NT) void attn_prefill_kernel(AttnArgs a) {
         if (a.gate) {
           const bf16x4 gz = *slot;
 #pragma unroll
-          for (int i = 0; i < 4; ++i)
-            v[i] *= __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * (float)gz[i]));
+          for (int i = 0; i < 4; ++i) v[i] *= gate_factor(a.gate_kind, (float)gz[i]);
         }
         bf16x4 o;
 #pragma unroll
@@ -556,7 +556,7 @@ void launch_attn_decoder_bf16(const Dims &d, const void *q, const void *k, const
                               hipStream_t st) {
   AttnArgs a = attn_args(d, q, k, c, cu, batch, total);
   a.wp = (const bf16 *)wp; a.gate = d.gate ? (const bf16 *)gate : nullptr; a.out = (bf16 *)out;
-  a.hpq = d.hpq; a.dh = d.dh; a.nh = d.nh;
+  a.hpq = d.hpq; a.dh = d.dh; a.nh = d.nh; a.gate_kind = d.gate;
   launch_attn<AttnNarrow, true>(a, d, batch, max_len, st);
 }
 
@@ -568,7 +568,7 @@ void launch_attn_chunk_bf16(const Dims &d, const void *q, const gta_cache &cache
   a.L = (bf16 *)L;
   if (fuse) {
     a.wp = (const bf16 *)wp; a.gate = d.gate ? (const bf16 *)gate : nullptr; a.out = (bf16 *)out;
-    a.hpq = d.hpq; a.dh = d.dh; a.nh = d.nh;
+    a.hpq = d.hpq; a.dh = d.dh; a.nh = d.nh; a.gate_kind = d.gate;
     launch_attn<AttnNarrow, true>(a, d, batch, max_chunk, st);
   } else if (d.dh == 128) {
     launch_attn<AttnWide, false>(a, d, batch, max_chunk, st);

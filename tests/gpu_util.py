@@ -36,10 +36,13 @@ def errors(got: np.ndarray, ref: np.ndarray):
     return float(np.abs(d).max()), float(np.linalg.norm(d) / max(np.linalg.norm(ref), 1e-300))
 
 
-def assert_close(got, ref, dtype, what=""):
+def assert_close(got, ref, dtype, what="", abs_scale=1.0):
+    """abs_scale widens the max-abs bound only (never the relative one): used where the reference values
+    are a known factor larger than the Sigmoid-gated outputs the bound was stated for."""
     assert np.all(np.isfinite(got)), f"{what}: non-finite values"
     ma, rr = errors(got, ref)
-    tol = TOL[dtype]
+    tol = dict(TOL[dtype])
+    tol["max_abs"] *= abs_scale
     assert ma <= tol["max_abs"] and rr <= tol["rel_rms"], \
         f"{what}: max_abs {ma:.3e} (tol {tol['max_abs']:.0e}), rel_rms {rr:.3e} (tol {tol['rel_rms']:.0e})"
     return ma, rr
@@ -66,8 +69,7 @@ def run_prefill(wl, wdev, x_np, cu_np=None, batch=None, max_seqlen=None, cache: 
                 slots=None, gate=True, workspace=None):
     """gta_prefill through the C ABI on numpy hidden states; returns the output tensor."""
     cfg = B.config_of(wl)
-    if not gate:
-        cfg.gate = B.GTA_GATE_OFF
+    cfg.gate = B.GATE_CODES[gate]
     total = x_np.shape[0]
     x = B.to_device(x_np, wl.dtype)
     if cu_np is not None:
@@ -92,8 +94,7 @@ def run_prefill(wl, wdev, x_np, cu_np=None, batch=None, max_seqlen=None, cache: 
 
 def run_decode(wl, wdev, x_np, cache: DeviceCache, slots=None, num_splits=0, gate=True):
     cfg = B.config_of(wl)
-    if not gate:
-        cfg.gate = B.GTA_GATE_OFF
+    cfg.gate = B.GATE_CODES[gate]
     batch = x_np.shape[0]
     x = B.to_device(x_np, wl.dtype)
     width = wl.d_model if wdev.get("wo") is not None else wl.n_heads * wl.head_dim
@@ -109,8 +110,7 @@ def run_decode(wl, wdev, x_np, cache: DeviceCache, slots=None, num_splits=0, gat
 def run_prefill_chunk(wl, wdev, x_np, cu_np, cache: DeviceCache, slots=None, gate=True):
     """gta_prefill_chunk through the C ABI: the chunks follow whatever the slots already hold."""
     cfg = B.config_of(wl)
-    if not gate:
-        cfg.gate = B.GTA_GATE_OFF
+    cfg.gate = B.GATE_CODES[gate]
     total = x_np.shape[0]
     x = B.to_device(x_np, wl.dtype)
     cu = torch.from_numpy(np.asarray(cu_np, dtype=np.int32)).cuda()
