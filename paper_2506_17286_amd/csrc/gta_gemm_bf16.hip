@@ -319,13 +319,28 @@ __device__ __forceinline__ bf16x4 pack4(float a, float b, float c, float d) {
 }
 
 // Workgroup -> tile mapping.  Consecutive workgroup ids land on different XCDs (8 of them, each
-// with its own L2); the remap gives every XCD a contiguous range of tiles (n fastest) so the
-// workgroups that run together on one XCD share X strips and weight strips in its L2.
+// with its own L2); the remap gives every XCD a contiguous range of whole row strips, and walks that
+// range in column panels of 4 tiles with the row strip as the fast index: the 32 workgroups that run
+// together on an XCD then share 8 X strips and 4 weight strips (instead of 2-3 and all of them), and
+// the weights are streamed from memory once per panel instead of once per round.
 __device__ __forceinline__ void tile_of_block(int ntn, int ntm, int &mt, int &nt) {
   const int nblk = ntn * ntm;
   int id = blockIdx.x;
   const int per = nblk / 8;
-  if (id < per * 8) id = (id % 8) * per + id / 8;
+  if (id < per * 8) {
+    const int x = id % 8, j = id / 8;
+    constexpr int PW = 4;
+    if (per % ntn == 0 && per / ntn >= 2) {
+      const int ms = per / ntn;                       // row strips of this XCD
+      const int full = (ntn / PW) * (ms * PW);        // tiles in complete panels
+      const int p = j < full ? j / (ms * PW) : ntn / PW;
+      const int within = j < full ? j % (ms * PW) : j - full;
+      mt = x * ms + within % ms;
+      nt = p * PW + within / ms;
+      return;
+    }
+    id = x * per + j;
+  }
   mt = id / ntn;
   nt = id % ntn;
 }
