@@ -101,6 +101,19 @@ def test_config5_varlen_prefill_bf16():
     _check_prefill_workload(wl, full_seqs=[int(order[0])], sampled_seqs=[int(order[-1]), int(order[7])])
 
 
+def test_paper_layer_prefill_b32_t2048_bf16():
+    """One attention layer of the paper's GTA-1B model at the batch of its efficiency runs: B=32, T=2048,
+    d_model 1280, 20 heads of 64 in 5 groups, one shared key, one latent of 128 (packed projection,
+    attention with the fused value decoder).  Oracle: every row of sequences 0 and 31, sampled rows of
+    sequences 7 and 16; caches of those four."""
+    _check_prefill_workload(W.PAPER_WORKLOADS[0], full_seqs=[0, 31], sampled_seqs=[7, 16])
+
+
+def test_paper_layer_decode_b64_t2048_bf16():
+    """The same layer, decode at batch 64 with 2048 cached tokens (narrow-row kernel).  Oracle on all 64."""
+    _check_decode_workload(W.PAPER_WORKLOADS[1], check_seqs=list(range(64)))
+
+
 @pytest.mark.parametrize("shape", ["1b", "wide", "paper", "paper_nq3"])
 def test_tuned_decode_ragged_contexts(shape):
     """The streaming decode kernels (wide rows, and the narrow-row kernel of the paper's own layer
