@@ -136,7 +136,7 @@ struct PipeMap {
   static constexpr int A_CPR = T::BK / 8, A_RPP = T::NT / A_CPR, A_PASSES = T::BM / A_RPP;
   static constexpr int B_CPR = T::BN / 8, B_RPP = T::NT / B_CPR, B_PASSES = T::BK / B_RPP;
   static constexpr int KSTEPS = T::BK / 16;
-  static_assert(T::BM % A_RPP == 0 && T::BK % B_RPP == 0 && A_PASSES == 8 && B_PASSES == 8, "staging");
+  static_assert(T::BM % A_RPP == 0 && T::BK % B_RPP == 0 && A_PASSES >= 1 && B_PASSES >= 1, "staging");
   static_assert(KSTEPS == 4, "the step schedule below is written for four k-steps per tile");
 };
 template <class T>
@@ -148,13 +148,17 @@ enum : int { SG_MFMA = 0x008, SG_VMEM_READ = 0x020, SG_DS_READ = 0x100, SG_DS_WR
 // writes and N_G global loads are dealt out over the remaining MFMAs.
 template <int N_MFMA, int N_FRAG, int N_W, int N_G>
 __device__ __forceinline__ void deal_step() {
-  static_assert(N_MFMA > N_FRAG, "schedule");
+  // MFMAs that carry fragment reads (one each if there are enough MFMAs, else half of the MFMAs with
+  // several reads each); the others carry the LDS writes and global loads
+  constexpr int F_SLOTS = N_MFMA > N_FRAG ? N_FRAG : N_MFMA / 2;
+  constexpr int RPS = (N_FRAG + F_SLOTS - 1) / F_SLOTS;
+  static_assert(F_SLOTS >= 1 && N_MFMA > F_SLOTS, "schedule");
 #pragma unroll
-  for (int i = 0; i < N_FRAG; ++i) {
+  for (int i = 0; i < F_SLOTS; ++i) {
     __builtin_amdgcn_sched_group_barrier(SG_MFMA, 1, 0);
-    __builtin_amdgcn_sched_group_barrier(SG_DS_READ, 1, 0);
+    __builtin_amdgcn_sched_group_barrier(SG_DS_READ, RPS, 0);
   }
-  constexpr int rest = N_MFMA - N_FRAG;
+  constexpr int rest = N_MFMA - F_SLOTS;
   constexpr int pw = (N_W + rest - 1) / rest, pg = (N_G + rest - 1) / rest;
 #pragma unroll
   for (int i = 0; i < rest; ++i) {
@@ -373,12 +377,13 @@ __device__ __forceinline__ void tile_to_lds(const f32x16 (&acc)[T::TN][T::TM], c
 }
 
 // calls f(row, chunk, value) for every 16-byte chunk (8 columns) of the staged tile: 32 lanes per row
-template <class F>
+template <int NT = 256, class F>
 __device__ __forceinline__ void for_each_out_chunk(const char *smem, F f) {
+  constexpr int RPP = NT / 32;   // rows per pass
   const int r0 = threadIdx.x >> 5, ch = threadIdx.x & 31;
 #pragma unroll 4
-  for (int it = 0; it < 32; ++it) {
-    const int r = it * 8 + r0;
+  for (int it = 0; it < 256 / RPP; ++it) {
+    const int r = it * RPP + r0;
     f(r, ch, *reinterpret_cast<const u32x4 *>(smem + r * kOutPitch + ch * 16));
   }
 }
@@ -816,18 +821,18 @@ __global__ __launch_bounds__(T::NT) void plain_gemm_kernel(PlainArgs a) {
   const int m0 = mt * T::BM, n0 = nt * T::BN;
   f32x16 acc[T::TN][T::TM];
   zero_acc<T>(acc);
-  if constexpr (T::TM == 4 && T::TN == 4) {
+  if constexpr (T::BM == 256 && T::BN == 256) {
     const unsigned boff = (unsigned)((threadIdx.x / (T::BN / 8)) * a.N + (threadIdx.x % (T::BN / 8)) * 8) * 2u;
     PipeStage<T> t0, t1;
     gemm_mainloop_pipe<T>(a.A + (int64_t)m0 * a.lda, a.lda, a.M - m0, a.B + n0, boff, a.N, a.K, smem, acc, t0, t1, NoTail{});
   } else {
     gemm_mainloop<T>(a.A, a.lda, a.M, m0, a.B, a.N, n0, a.K, smem, acc);
   }
-  if constexpr (T::TM == 4 && T::TN == 4) {
+  if constexpr (T::BM == 256 && T::BN == 256) {
     __syncthreads();
     tile_to_lds<T>(acc, smem);
     __syncthreads();
-    for_each_out_chunk(smem, [&](int r, int ch, u32x4 v) {
+    for_each_out_chunk<T::NT>(smem, [&](int r, int ch, u32x4 v) {
       if (m0 + r < a.M) *reinterpret_cast<u32x4 *>(a.C + (int64_t)(m0 + r) * a.N + n0 + ch * 8) = v;
     });
     return;

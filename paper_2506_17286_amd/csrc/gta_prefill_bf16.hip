@@ -169,7 +169,8 @@ __global__ __launch_bounds__(T::NT) void attn_prefill_kernel(AttnArgs a) {
   // (such keys are in the future of every valid query and are masked)
   u32x4 rk, rc[T::C_LOADS];
   const int k_row = tid / T::K_CPR, k_ch = tid % T::K_CPR, c_row = tid / T::C_CPR, c_ch = tid % T::C_CPR;
-  const bool k_loader = tid < T::K_CHUNKS, c_loader = tid < T::C_CHUNKS;   // narrow tiles have fewer chunks than threads
+  // narrow tiles have fewer chunks than threads (no predicate at all where every thread loads)
+  const bool k_loader = T::K_CHUNKS >= T::NT || tid < T::K_CHUNKS, c_loader = T::C_CHUNKS >= T::NT || tid < T::C_CHUNKS;
   auto gload = [&](int t) {
     const int j0 = t * T::BK;
     if (k_loader) {
@@ -298,12 +299,31 @@ __global__ __launch_bounds__(T::NT) void attn_prefill_kernel(AttnArgs a) {
   const int t_main = min(nb_w, qa0 >> 5) - 1;   // iterations 0 .. t_main-1
 #pragma unroll 1
   for (; t < t_main; ++t) {
+    // The fragment reads of the first score MFMAs and of the first two map-times-latent MFMAs go out
+    // before anything else, so that the MFMAs below do not each wait for an LDS round trip; the second
+    // half of the key fragments follows behind the first two score MFMAs.
+    constexpr int KS = T::DH / 16, KS1 = KS / 2;
+    const char *kst = smem + nxt + koff;
+    bf16x8 kf[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS1; ++ks) kf[ks] = *reinterpret_cast<const bf16x8 *>(kst + ks * 32);
+    __builtin_amdgcn_sched_barrier(0);
     sstore(smem + fre);
     gload(t + 3);
     rescale();
     f32x16 s;
-    scores(smem + nxt, s);
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s[r] = 0.f;
     __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      if (ks == 1) {
+#pragma unroll
+        for (int k2 = KS1; k2 < KS; ++k2) kf[k2] = *reinterpret_cast<const bf16x8 *>(kst + k2 * 32);
+      }
+      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[ks], s, 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
     // 2 * NDLB steps, each one MFMA of block t (latent fragment i, read two steps earlier), the
     // transpose reads of fragment i+2 and a slice of the softmax arithmetic of block t+1 (16 slices
     // dealt evenly over the steps); the scheduling barrier after every step pins this order, so each
@@ -317,9 +337,10 @@ __global__ __launch_bounds__(T::NT) void attn_prefill_kernel(AttnArgs a) {
       s16x8 c8 = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
       return __builtin_bit_cast(bf16x8, c8);
     };
-    bf16x8 cf[NS + 2], pn[2];
-    cf[0] = cread(0);
-    cf[1] = cread(1);
+    constexpr int LA = 2;   // latent fragments in flight ahead of their MFMA (3 measured no better)
+    bf16x8 cf[NS + LA], pn[2];
+#pragma unroll
+    for (int i = 0; i < LA; ++i) cf[i] = cread(i);
     float b0, b1, b2, b3, b4, m_new = 0.f, negm = 0.f, ps = 0.f;
     const bf16x2 ones = {(bf16)1.0f, (bf16)1.0f};
     auto soft_slice = [&](int k) {
@@ -350,7 +371,7 @@ __global__ __launch_bounds__(T::NT) void attn_prefill_kernel(AttnArgs a) {
     };
 #pragma unroll
     for (int i = 0; i < NS; ++i) {
-      if (i + 2 < NS) cf[i + 2] = cread(i + 2);
+      if (i + LA < NS) cf[i + LA] = cread(i + LA);
       acc[i % T::NDLB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cf[i], pf[i / T::NDLB], acc[i % T::NDLB], 0, 0, 0);
 #pragma unroll
       for (int k = i * SPS; k < (i + 1) * SPS; ++k) soft_slice(k);
