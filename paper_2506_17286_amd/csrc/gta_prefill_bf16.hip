@@ -196,15 +196,17 @@ __global__ __launch_bounds__(T::NT) void attn_prefill_kernel(AttnArgs a) {
   const int koff = ln * T::K_PITCH + h * 16;
   const int coff = T::K_BYTES + (4 * h + ((lane & 15) >> 2)) * T::C_PITCH + (((lane >> 4) & 1) * 16 + (lane & 3) * 4) * 2;
 
-  // scores S^T of one 32-key block (raw, unscaled)
+  // scores S^T of one 32-key block (raw, unscaled); all key fragments are requested before the first
+  // MFMA so that the chain of MFMAs pays one LDS round trip, not one per fragment
   auto scores = [&](const char *st, f32x16 &s) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) s[r] = 0.f;
+    bf16x8 kf[T::DH / 16];
 #pragma unroll
-    for (int ks = 0; ks < T::DH / 16; ++ks) {
-      const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(st + koff + ks * 32);
-      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s, 0, 0, 0);
-    }
+    for (int ks = 0; ks < T::DH / 16; ++ks) kf[ks] = *reinterpret_cast<const bf16x8 *>(st + koff + ks * 32);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int ks = 0; ks < T::DH / 16; ++ks) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[ks], s, 0, 0, 0);
   };
   // keys after the lane's query are masked in a block that touches the diagonal
   auto mask = [&](f32x16 &s, int jb) {
