@@ -36,11 +36,11 @@ PEAK_HBM_GBPS = 8000.0        # MI355X HBM3E
 # (profiles/bench_<workload>.txt hold the commands and the raw readings).  Counters cannot be
 # read from inside this process, so these are the last recorded values, not live ones.
 RECORDED_TRAFFIC_BYTES = {
-    ("decode_b8_32k_bf16", "decode_attn_kernel"): 537.79e6 + 4.22e6,
-    ("decode_b64_8k_bf16", "decode_attn_kernel"): 1079.05e6 + 4.26e6,
-    ("prefill_1b_bf16", "attn_prefill_kernel"): 93.78e6 + 67.11e6,
-    ("varlen_prefill_bf16", "attn_prefill_kernel"): 20328.74e6 + 1989.15e6,
-    ("gta1b_prefill_b32_t2048", "attn_prefill_kernel"): 164.49e6 + 104.13e6,
+    ("decode_b8_32k_bf16", "decode_attn_kernel"): 537.78e6 + 4.22e6,
+    ("decode_b64_8k_bf16", "decode_attn_kernel"): 1079.08e6 + 4.26e6,
+    ("prefill_1b_bf16", "attn_prefill_kernel"): 93.68e6 + 67.11e6,
+    ("varlen_prefill_bf16", "attn_prefill_kernel"): 17472.04e6 + 1989.15e6,
+    ("gta1b_prefill_b32_t2048", "attn_prefill_kernel"): 167.66e6 + 104.13e6,
     ("gta1b_decode_b64_t2048", "decode_attn_kernel"): 52.52e6 + 1.35e6,
 }
 
