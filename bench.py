@@ -8,7 +8,8 @@ The headline metric names two things, so both are measured in every run:
     gta_prefill call and fraction of the bf16 MFMA peak -- under the key "prefill".
 The batched decode workload (B=64, 8192 cached tokens) is reported under "decode_b64_8k" and the
 ragged packed prefill (16 sequences of 512..16384 tokens, H=4096, d_l=1024) under "varlen_prefill".
-"paper_layer_gta1b" holds one attention layer of the paper's own GTA-1B model (H=1280, 20 heads of 64
+"chunked_prefill" is gta_prefill_chunk on the prefill workload's shape: 2048 new tokens per sequence behind
+2048 cached ones.  "paper_layer_gta1b" holds one attention layer of the paper's own GTA-1B model (H=1280, 20 heads of 64
 in 5 groups, one shared key, one latent of 128) at the batch sizes of its efficiency runs: prefill of
 32 x 2048 tokens and a decode step at batch 64 with 2048 cached tokens.
 
@@ -184,6 +185,47 @@ def bench_prefill(wl, steps, warmup, want_cpu_baseline):
     return res
 
 
+def bench_prefill_chunk(wl, prefix, steps, warmup):
+    """Chunked prefill: every slot already holds `prefix` tokens, one call adds the remaining seqlen - prefix
+    tokens of every sequence (gta_prefill_chunk).  Flops: projections and decoder of the chunk's tokens, the
+    causal pairs the chunk's rows have with the whole sequence."""
+    import numpy as np
+    import torch
+    from paper_2506_17286_amd import binding as B, workloads as W, costmodel as cm
+    cfg = B.config_of(wl)
+    lens, cu, w, x_np = W.prefill_inputs(wl)
+    wdev = {k: B.to_device(v, wl.dtype) for k, v in w.items()}
+    gw = B.make_weights(wdev)
+    T, n = wl.seqlen, wl.seqlen - prefix
+    x = B.to_device(x_np, wl.dtype).view(wl.batch, T, wl.d_model)
+    xp, xc = x[:, :prefix].reshape(-1, wl.d_model).contiguous(), x[:, prefix:].reshape(-1, wl.d_model).contiguous()
+    kw, cw = wl.kv_width
+    k = torch.zeros((wl.batch, T, kw), dtype=x.dtype, device="cuda")
+    c = torch.zeros((wl.batch, T, cw), dtype=x.dtype, device="cuda")
+    seq = torch.zeros(wl.batch, dtype=torch.int32, device="cuda")
+    st = torch.zeros(wl.batch, dtype=torch.int32, device="cuda")
+    cache = B.make_cache(k, c, seq, st)
+    outp = torch.empty((wl.batch * prefix, wl.n_heads * wl.head_dim), dtype=x.dtype, device="cuda")
+    outc = torch.empty((wl.batch * n, wl.n_heads * wl.head_dim), dtype=x.dtype, device="cuda")
+    ws = B.alloc_workspace(max(B.gta_workspace_bytes(cfg, B.GTA_MODE_PREFILL, wl.batch, wl.batch * prefix, prefix),
+                               B.gta_workspace_bytes(cfg, B.GTA_MODE_PREFILL_CHUNK, wl.batch, wl.batch * n, n)))
+    B.gta_prefill(cfg, gw, xp, None, wl.batch, wl.batch * prefix, prefix, cache, None, outp, ws)
+
+    def step(i):
+        seq.fill_(prefix)          # every timed call starts from the same prefix (a tiny fill kernel)
+        B.gta_prefill_chunk(cfg, gw, xc, None, wl.batch, wl.batch * n, n, cache, None, outc, ws)
+
+    sec = _time_steps(step, steps, warmup)
+    assert int(st.abs().sum()) == 0 and int(seq[0]) == T
+    pairs = wl.batch * (n * prefix + n * (n + 1) // 2)
+    tok = wl.batch * n
+    wtot = (wl.n_qgroups + wl.n_kgroups) * wl.head_dim + wl.n_cgroups * wl.latent_dim + wl.n_heads * wl.head_dim
+    fl = 2 * tok * wl.d_model * wtot + 2 * wl.n_qgroups * (wl.head_dim + wl.latent_dim) * pairs \
+        + 2 * tok * wl.n_heads * wl.latent_dim * wl.head_dim
+    return {"workload": f"{wl.name}: {prefix} cached + {n} new tokens per sequence", "ms_per_step": sec * 1e3,
+            "tokens_per_s": tok / sec, "tflops": fl / sec / 1e12, "algorithmic_flops": fl}
+
+
 def bench_attention_comparator(steps):
     """Causal attention stage alone (gta_prefill_attention) at 32 x 2048 tokens for the paper's GTA-1B layer
     and for the GQA-1B layer written as the degenerate GTA setting (one map per head, 5 key and 5 value
@@ -340,6 +382,9 @@ def main():
         pre = bench_prefill(W.by_name("prefill_1b_bf16"), args.steps, args.warmup, cpu)
     if args.only in (None, "decode8k"):
         dec8 = bench_decode(W.by_name("decode_b64_8k_bf16"), args.steps, args.warmup, False)
+    chk = None
+    if args.only in (None, "prefill"):  # second half of every sequence of the prefill workload behind the first
+        chk = bench_prefill_chunk(W.by_name("prefill_1b_bf16"), 2048, args.steps, args.warmup)
     if args.only in (None, "varlen"):   # ragged packed batch, 16 sequences of 512..16384 tokens, wider model
         var = bench_prefill(W.by_name("varlen_prefill_bf16"), min(args.steps, 10), min(args.warmup, 3), False)
     if args.only in (None, "paper"):    # one attention layer of the paper's GTA-1B model (heads of 64, d_l = 128)
@@ -372,6 +417,8 @@ def main():
         line["decode_b64_8k"] = dec8
     if var is not None and main_res is not var:
         line["varlen_prefill"] = var
+    if chk is not None:
+        line["chunked_prefill"] = chk
     if pap is not None:
         line["paper_layer_gta1b"] = pap if main_res is not pap["prefill"] else {k: v for k, v in pap.items() if k != "prefill"}
     print(json.dumps(line))
