@@ -951,6 +951,136 @@ __global__ __launch_bounds__(512) void decode_tail1_kernel(Dims d, const float *
   }
 }
 
+// The tail for the narrow shapes (d_l = 128, d_h = 64, 1 / 2 / 4 heads per map group, at most 32 splits):
+// one workgroup finishes the heads of ONE map group for two sequences, and, like the kernel above, asks
+// for everything it reads -- split statistics, partial accumulators, the group's decoder matrices, the
+// gate partials -- before it uses any of it.
+template <typename TO, int HPQ>
+__global__ __launch_bounds__(256) void decode_tail_narrow_kernel(Dims d, const float *__restrict__ pacc,
+                                                                 const float *__restrict__ pml,
+                                                                 const int32_t *__restrict__ oldlen, int splits,
+                                                                 int batch, const float *__restrict__ G, int g_nsum,
+                                                                 int64_t g_kstride, int g_ld,
+                                                                 const bf16 *__restrict__ wp, TO *__restrict__ out,
+                                                                 int32_t *seq_lens, int32_t *status,
+                                                                 const int32_t *__restrict__ slots, int max_batch) {
+  constexpr int DL = 128, DH = 64, MAXS = 32, ROWS = 2;
+  constexpr int NPH = 256 / (HPQ * 8), APC = DL / NPH;      // latent phases per head, latent rows per phase
+  constexpr int NOUT = ROWS * HPQ * DH / 256 > 0 ? ROWS * HPQ * DH / 256 : 1;   // outputs per thread
+  __shared__ float wt[ROWS][MAXS];
+  __shared__ float4 red4[4][ROWS * DL / 4];
+  __shared__ float Ls[ROWS][DL];
+  __shared__ float redz[NPH][ROWS][HPQ * DH];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int g = blockIdx.x, b0 = blockIdx.y * ROWS;
+  auto live = [&](int r) { return b0 + r < batch && oldlen[b0 + r] >= 0; };
+  // ---- all loads
+  float gz[NOUT];
+#pragma unroll
+  for (int o = 0; o < NOUT; ++o) {
+    gz[o] = 0.f;
+    const int i = tid + o * 256, r = i / (HPQ * DH), c = i % (HPQ * DH);
+    if (d.gate && i < ROWS * HPQ * DH && live(r))
+      for (int k = 0; k < g_nsum; ++k) gz[o] += G[k * g_kstride + (int64_t)(b0 + r) * g_ld + g * HPQ * DH + c];
+  }
+  const int64_t ms = (int64_t)d.nq * 2;
+  float m_s = -INFINITY, l_s = 0.f;
+  if (wave == 0) {   // lane = (row, split)
+    const int r = lane / MAXS, sp = lane % MAXS;
+    if (live(r) && sp < splits) {
+      const float *pm = pml + ((int64_t)(b0 + r) * splits * d.nq + g) * 2 + sp * ms;
+      m_s = pm[0]; l_s = pm[1];
+    }
+  }
+  const int item = tid % (ROWS * DL / 4), sph = tid / (ROWS * DL / 4);   // (row, 4 columns), one of 4 split phases
+  const int ir = item / (DL / 4), ic4 = item % (DL / 4);
+  float4 v[MAXS / 4];
+  {
+    const bool lv = live(ir);
+    const float4 *pa = reinterpret_cast<const float4 *>(pacc + ((int64_t)(lv ? b0 + ir : 0) * splits * d.nq + g) * DL) + ic4;
+    const int64_t as4 = (int64_t)d.nq * DL / 4;
+#pragma unroll
+    for (int u = 0; u < MAXS / 4; ++u) {
+      const int sp = sph + 4 * u;
+      v[u] = (lv && sp < splits) ? pa[sp * as4] : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+  }
+  const int cg = tid % 8, ph = (tid / 8) % NPH, hl = tid / (8 * NPH);   // 8 output columns, latent phase, head
+  bf16x8 w8[APC];
+  {
+    const bf16 *wb = wp + (int64_t)(g * HPQ + hl) * DL * DH + cg * 8;
+#pragma unroll
+    for (int i = 0; i < APC; ++i) w8[i] = *reinterpret_cast<const bf16x8 *>(wb + (int64_t)(ph * APC + i) * DH);
+  }
+  if (g == 0 && tid < ROWS && b0 + tid < batch) {
+    const int b = b0 + tid, slot = slots ? slots[b] : b;
+    if (slot >= 0 && slot < max_batch) {
+      if (oldlen[b] >= 0) seq_lens[slot] = oldlen[b] + 1;
+      else status[slot] = GTA_ERR_CACHE_FULL;
+    }
+  }
+  // ---- log-sum-exp weights of the splits: one 32-lane half of wave 0 per row
+  if (wave == 0) {
+    float mx = m_s;
+#pragma unroll
+    for (int o = 16; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
+    const float e = m_s > -INFINITY ? exp2f(m_s - mx) : 0.f;
+    float ls = e * l_s;
+#pragma unroll
+    for (int o = 16; o > 0; o >>= 1) ls += __shfl_xor(ls, o, 64);
+    wt[lane / MAXS][lane % MAXS] = ls > 0.f ? e / ls : 0.f;
+  }
+  __syncthreads();
+  {
+    float4 a4 = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+    for (int u = 0; u < MAXS / 4; ++u) {
+      const int sp = sph + 4 * u;
+      const float w = sp < splits ? wt[ir][sp] : 0.f;
+      if (w != 0.f) {   // a split without rows has weight 0 and an unwritten accumulator
+        a4.x = fmaf(w, v[u].x, a4.x); a4.y = fmaf(w, v[u].y, a4.y);
+        a4.z = fmaf(w, v[u].z, a4.z); a4.w = fmaf(w, v[u].w, a4.w);
+      }
+    }
+    red4[sph][item] = a4;
+  }
+  __syncthreads();
+  if (tid < ROWS * DL / 4) {
+    const float4 x0 = red4[0][tid], x1 = red4[1][tid], x2 = red4[2][tid], x3 = red4[3][tid];
+    float *dst = &Ls[0][0] + tid * 4;
+    dst[0] = (x0.x + x1.x) + (x2.x + x3.x); dst[1] = (x0.y + x1.y) + (x2.y + x3.y);
+    dst[2] = (x0.z + x1.z) + (x2.z + x3.z); dst[3] = (x0.w + x1.w) + (x2.w + x3.w);
+  }
+  __syncthreads();
+  // ---- value decoder (Sec. 3.2) from the prefetched matrices, latent phases summed through LDS
+#pragma unroll
+  for (int r = 0; r < ROWS; ++r) {
+    float z[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) z[e] = 0.f;
+#pragma unroll
+    for (int i = 0; i < APC; ++i) {
+      const float lv = Ls[r][ph * APC + i];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) z[e] = fmaf(lv, (float)w8[i][e], z[e]);
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) redz[ph][r][hl * DH + cg * 8 + e] = z[e];
+  }
+  __syncthreads();
+#pragma unroll
+  for (int o = 0; o < NOUT; ++o) {
+    const int i = tid + o * 256, r = i / (HPQ * DH), c = i % (HPQ * DH);
+    if (i >= ROWS * HPQ * DH || b0 + r >= batch) continue;
+    float acc = 0.f;
+#pragma unroll
+    for (int q = 0; q < NPH; ++q) acc += redz[q][r][c];
+    if (d.gate == kGateSigmoid) acc *= 1.0f / (1.0f + __expf(-gz[o]));
+    else if (d.gate) acc *= gate_factor(d.gate, gz[o]);
+    out[(int64_t)(b0 + r) * d.wg_w + g * HPQ * DH + c] = live(r) ? (TO)acc : (TO)0.f;
+  }
+}
+
 // where the gate pre-activations come from: `nsum` terms at stride `kstride`, row pitch `ld`
 struct GateSrc { const float *g; int nsum; int64_t kstride; int ld; };
 
@@ -974,6 +1104,18 @@ void launch_tail_any(const Dims &d, const float *pacc, const float *pml, const D
     decode_tail1_kernel<TO><<<dim3(d.nh, batch), 512, 0, st>>>(d, pacc, pml, ws.oldlen, ws.splits, gs.g, gs.nsum,
                                                                gs.kstride, gs.ld, wp, out, cache.seq_lens,
                                                                cache.status, slots, cache.max_batch);
+    return;
+  }
+  if (d.dl == 128 && d.dh == 64 && (d.hpq == 1 || d.hpq == 2 || d.hpq == 4) && ws.splits <= 32) {
+    const dim3 grid(d.nq, (batch + 1) / 2);
+#define GTA_TAIL_NARROW(HPQ)                                                                                      \
+    decode_tail_narrow_kernel<TO, HPQ><<<grid, 256, 0, st>>>(d, pacc, pml, ws.oldlen, ws.splits, batch, gs.g, gs.nsum, \
+                                                            gs.kstride, gs.ld, wp, out, cache.seq_lens, cache.status, \
+                                                            slots, cache.max_batch)
+    if (d.hpq == 4) GTA_TAIL_NARROW(4);
+    else if (d.hpq == 2) GTA_TAIL_NARROW(2);
+    else GTA_TAIL_NARROW(1);
+#undef GTA_TAIL_NARROW
     return;
   }
   if (rows >= 8) launch_tail<TO, 8>(d, pacc, pml, ws, batch, gs, wp, out, cache, slots, st);

@@ -114,7 +114,7 @@ def test_paper_layer_decode_b64_t2048_bf16():
     _check_decode_workload(W.PAPER_WORKLOADS[1], check_seqs=list(range(64)))
 
 
-@pytest.mark.parametrize("shape", ["1b", "wide", "paper", "paper_nq3"])
+@pytest.mark.parametrize("shape", ["1b", "wide", "paper", "paper_nq3", "paper_nq6"])
 def test_tuned_decode_ragged_contexts(shape):
     """The streaming decode kernels (wide rows, and the narrow-row kernel of the paper's own layer
     shapes) on ragged context lengths incl. 0, 1, block tails and empty splits, every output element
@@ -123,6 +123,8 @@ def test_tuned_decode_ragged_contexts(shape):
         base = W.PAPER_WORKLOADS[1]
     elif shape == "paper_nq3":   # the 160M-class layer: 12 heads of 64 in 3 groups
         base = W.scaled(W.PAPER_WORKLOADS[1], d_model=768, n_heads=12, n_qgroups=3)
+    elif shape == "paper_nq6":   # its sibling with 6 groups (two heads per group)
+        base = W.scaled(W.PAPER_WORKLOADS[1], d_model=768, n_heads=12, n_qgroups=6)
     else:
         base = W.WORKLOADS[2] if shape == "1b" else W.scaled(W.WORKLOADS[4], kind="decode", min_seqlen=None)
     ctx = [0, 1, 7, 8, 31, 32, 33, 255, 777, 1500]
