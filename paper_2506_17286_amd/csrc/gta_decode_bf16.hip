@@ -397,8 +397,10 @@ __global__ __launch_bounds__(256, S::OCC) void decode_attn_kernel(DecAttnArgs a,
 // layout (lane l: rows l/16 and 4 + l/16 of the step), so a wave runs four independent online-softmax
 // streams (rows c and c+4 of every step, c = 0..3): the two key-layout lane groups of a stream are 32
 // lanes apart and agree on its statistics with one exchange, and the latent-layout lanes of stream c
-// fetch its two probabilities and its rescale factor from lane 8c.  Streams, waves and splits are
-// merged with the usual log-sum-exp weights.  Same three call modes as the kernel above.
+// fetch its two probabilities (one bf16 pair) and its rescale factor from lane 8c.  Scores and the
+// probability-times-latent update are bf16 dot products with fp32 sums (v_dot2_f32_bf16, two rows per
+// instruction), which is what keeps the kernel from being bound by VALU issue.  Streams, waves and
+// splits are merged with the usual log-sum-exp weights.  Same three call modes as the kernel above.
 template <int NQ>
 __global__ __launch_bounds__(256) void decode_narrow_kernel(DecAttnArgs a, RopeFreq rf) {
   constexpr int DH = 64, DL = 128, WQ = NQ * DH, WK = DH, WC = DL, half = DH / 2, R = 8;
@@ -506,42 +508,67 @@ __global__ __launch_bounds__(256) void decode_narrow_kernel(DecAttnArgs a, RopeF
   }
   __syncthreads();
 
-  float qf[NQ][8];   // this lane's eighth of every query
+  // this lane's eighth of every query as bf16 pairs: the scores are bf16 dot products with fp32 sums
+  // (v_dot2_f32_bf16), the precision the prefill kernels give the same product
+  typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+  bf16x2 qh[NQ][4];
 #pragma unroll
   for (int g = 0; g < NQ; ++g)
 #pragma unroll
-    for (int e = 0; e < 8; ++e) qf[g][e] = qs[g * DH + (lane & 7) * 8 + e];
+    for (int w = 0; w < 4; ++w) {
+      bf16x2 t;
+      t[0] = (bf16)qs[g * DH + (lane & 7) * 8 + 2 * w];
+      t[1] = (bf16)qs[g * DH + (lane & 7) * 8 + 2 * w + 1];
+      qh[g][w] = t;
+    }
+  const bf16x2 ones = {(bf16)1.0f, (bf16)1.0f};
   const int src = (lane >> 4) << 3;   // key-layout lane that holds this latent-layout lane's stream
   auto compute = [&](const Blk &bk, int nv) {
-    float kf[8], p[NQ], p2[NQ], corr[NQ];
-    unpack8(bk.k, kf);
+    float corr[NQ];
+    bf16x2 pk[NQ];   // (probability of the stream's first row, of its second row), rounded as the MFMA paths do
+    const unsigned kw[4] = {bk.k.x, bk.k.y, bk.k.z, bk.k.w};
     const bool valid = (lane >> 3) < nv;
+    bool changed = false;
 #pragma unroll
     for (int g = 0; g < NQ; ++g) {
       float sc = 0.f;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) sc = fmaf(qf[g][e], kf[e], sc);
+      for (int w = 0; w < 4; ++w) sc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, kw[w]), qh[g][w], sc, false);
       sc = group_sum<8>(sc);
       sc = valid ? sc : -INFINITY;
       const float sc2 = __shfl_xor(sc, 32, 64);              // the stream's other row of this step
       const float mn = fmaxf(m[g], fmaxf(sc, sc2));
       const float ref = mn > -INFINITY ? mn : 0.f;            // a stream that has seen no row yet
       corr[g] = fast_exp2(m[g] - ref);
-      p[g] = fast_exp2(sc - ref);
-      p2[g] = fast_exp2(sc2 - ref);
-      l[g] = fmaf(l[g], corr[g], p[g] + p2[g]);
+      changed |= mn != m[g];
+      bf16x2 t;
+      t[0] = (bf16)fast_exp2(sc - ref);
+      t[1] = (bf16)fast_exp2(sc2 - ref);
+      pk[g] = t;
+      l[g] = __builtin_amdgcn_fdot2_f32_bf16(t, ones, l[g] * corr[g], false);   // the sum of the rounded values
       m[g] = mn;
     }
-    float c0[8], c1[8];
-    unpack8(bk.c0, c0);
-    unpack8(bk.c1, c1);
+    // latent elements of the step's two rows side by side: word e = (row A's element e, row B's element e)
+    const unsigned ca[4] = {bk.c0.x, bk.c0.y, bk.c0.z, bk.c0.w}, cb[4] = {bk.c1.x, bk.c1.y, bk.c1.z, bk.c1.w};
+    bf16x2 cx[8];
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      cx[2 * w] = __builtin_bit_cast(bf16x2, __builtin_amdgcn_perm(cb[w], ca[w], 0x05040100u));
+      cx[2 * w + 1] = __builtin_bit_cast(bf16x2, __builtin_amdgcn_perm(cb[w], ca[w], 0x07060302u));
+    }
+    const bool any_changed = __any(changed);
 #pragma unroll
     for (int g = 0; g < NQ; ++g) {
-      // lane src sits in the key layout on row src/8 = lane/16 (< 4): its p is the first latent load's
-      // probability, its p2 the second's
-      const float pA = __shfl(p[g], src, 64), pB = __shfl(p2[g], src, 64), cr = __shfl(corr[g], src, 64);
+      // lane src sits in the key layout on row src/8 = lane/16 (< 4): its pair is (first latent load's
+      // probability, second's)
+      const bf16x2 pp = __builtin_bit_cast(bf16x2, __shfl(__builtin_bit_cast(int, pk[g]), src, 64));
+      if (any_changed) {   // wave-uniform
+        const float cr = __shfl(corr[g], src, 64);
 #pragma unroll
-      for (int e = 0; e < 8; ++e) acc[g][e] = fmaf(pB, c1[e], fmaf(pA, c0[e], acc[g][e] * cr));
+        for (int e = 0; e < 8; ++e) acc[g][e] *= cr;
+      }
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[g][e] = __builtin_amdgcn_fdot2_f32_bf16(cx[e], pp, acc[g][e], false);
     }
   };
   int blk = wave;
