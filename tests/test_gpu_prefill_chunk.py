@@ -86,6 +86,33 @@ def test_several_chunks_in_a_row(shape):
     U.assert_close(U.f64(cache.c)[1, :32], Cref[700:], wl.dtype, "C cache")
 
 
+@pytest.mark.parametrize("shape", ["1b", "paper"])
+def test_empty_sequences_in_a_packed_batch(shape):
+    """Sequences without tokens inside a packed batch (equal consecutive offsets): a fresh prefill sets their
+    length to 0, a chunked prefill leaves their slot as it is; the other sequences are unaffected."""
+    lens = [40, 0, 70, 0]
+    wl = W.scaled(_base(shape), batch=4, seqlen=70, min_seqlen=None)
+    w, cu, x = _inputs(wl, lens)
+    wdev = U.upload_weights(w, wl.dtype)
+    cache = U.DeviceCache(wl, 4, 128, fill=-3.0)
+    cache.seq_lens[1] = 9
+    ref, Kref, Cref = orc.prefill(U.oracle_config(wl), U.oracle_weights(w), x, np.array([0, 40, 110], dtype=np.int32))
+    out = U.run_prefill(wl, wdev, x, cu, cache=cache)
+    U.assert_close(U.f64(out), ref, wl.dtype, "prefill with empty sequences")
+    assert cache.seq_lens.cpu().tolist() == [40, 0, 70, 0]
+    # now a chunk for sequences 0 and 3 only; 1 and 2 get nothing
+    lens2 = [5, 0, 0, 3]
+    w2, cu2, x2 = w, np.concatenate([[0], np.cumsum(lens2)]).astype(np.int32), W.draw_hidden(wl, W.make_rng(W.scaled(wl, seed=77)), 8)
+    out2 = U.run_prefill_chunk(wl, wdev, x2, cu2, cache)
+    full0 = np.concatenate([x[:40], x2[:5]])
+    r0, _, _ = orc.prefill_sequence(U.oracle_config(wl), U.oracle_weights(w), full0)
+    r3, _, _ = orc.prefill_sequence(U.oracle_config(wl), U.oracle_weights(w), x2[5:])
+    U.assert_close(U.f64(out2)[:5], r0[40:], wl.dtype, "chunk behind 40 rows")
+    U.assert_close(U.f64(out2)[5:], r3, wl.dtype, "chunk on an empty slot")
+    assert cache.seq_lens.cpu().tolist() == [45, 0, 70, 3]
+    assert np.all(cache.status.cpu().numpy() == 0)
+
+
 def test_chunk_that_does_not_fit_is_skipped():
     """A chunk that would overflow its slot stores nothing, returns zero rows and flags the slot; the
     other sequence of the call is unaffected."""
