@@ -42,7 +42,7 @@ RECORDED_TRAFFIC_BYTES = {
     ("prefill_1b_bf16", "attn_prefill_kernel"): 93.68e6 + 67.11e6,
     ("varlen_prefill_bf16", "attn_prefill_kernel"): 17472.04e6 + 1989.15e6,
     ("gta1b_prefill_b32_t2048", "attn_prefill_kernel"): 167.66e6 + 104.13e6,
-    ("gta1b_decode_b64_t2048", "decode_attn_kernel"): 52.52e6 + 1.35e6,
+    ("gta1b_decode_b64_t2048", "decode_attn_kernel"): 52.51e6 + 1.35e6,
 }
 
 
