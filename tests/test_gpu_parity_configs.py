@@ -147,6 +147,29 @@ def test_tuned_decode_ragged_contexts(shape):
         assert np.array_equal(cache.seq_lens.cpu().numpy(), sl)
 
 
+@pytest.mark.parametrize("shape,batch", [("1b", 70), ("1b", 37), ("paper", 131)])
+def test_tuned_decode_batches_that_do_not_fill_the_last_workgroup(shape, batch):
+    """Batch sizes that are not multiples of the sequences a tail workgroup takes (8, 4, 2): short ragged
+    contexts, every output element against the oracle."""
+    base = W.WORKLOADS[2] if shape == "1b" else W.PAPER_WORKLOADS[1]
+    ctx = [(13 * b + 3) % 97 for b in range(batch)]
+    wl = W.scaled(base, batch=batch, seqlen=max(ctx))
+    rng = W.make_rng(wl)
+    w = W.draw_weights(wl, rng)
+    x = W.draw_hidden(wl, rng, batch)
+    max_seq = max(ctx) + 1
+    k_np, c_np = W.draw_cache(wl, rng, batch, max_seq)
+    wdev = U.upload_weights(w, wl.dtype)
+    cache = U.DeviceCache(wl, batch, max_seq, k=B.to_device(k_np, wl.dtype), c=B.to_device(c_np, wl.dtype),
+                          seq_lens=torch.tensor(ctx, dtype=torch.int32).cuda())
+    out = U.run_decode(wl, wdev, x, cache)
+    sl = np.array(ctx, dtype=np.int32); st = np.zeros(batch, dtype=np.int32)
+    ref = orc.decode(U.oracle_config(wl), U.oracle_weights(w), x, k_np.astype(np.float64), c_np.astype(np.float64),
+                     sl, st, list(range(batch)))
+    U.assert_close(U.f64(out), ref, wl.dtype, f"decode {shape} batch {batch}")
+    assert np.array_equal(cache.seq_lens.cpu().numpy(), sl)
+
+
 @pytest.mark.parametrize("shape,with_wo", [("1b", False), ("1b", True), ("wide", False), ("paper", False),
                                            ("paper", True), ("packed128", False), ("slim", False)])
 def test_tuned_prefill_ragged_small(shape, with_wo):
