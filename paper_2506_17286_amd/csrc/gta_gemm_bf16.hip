@@ -512,30 +512,36 @@ __global__ __launch_bounds__(T::NT) void proj_gemm_kernel(ProjArgs a) {
 // 256-column tile may straddle Q | K | C | gate: this serves output widths that are multiples of 64
 // but not of 256 (heads of 64, a single shared key).  Columns are routed to their outputs per
 // 64-column group for RoPE (a head never straddles a group) and per 16-byte chunk for the stores.
-__global__ void pack_weights_kernel(ProjArgs a, int wtot, bf16 *dst) {
-  const int cpr = wtot / 8;   // 16-byte chunks per packed row
+// The packed row is padded with zero columns to a multiple of 256 (wpad); the last tile computes
+// them and stores nothing for them.
+__global__ void pack_weights_kernel(ProjArgs a, int wtot, int wpad, bf16 *dst) {
+  const int cpr = wpad / 8;   // 16-byte chunks per packed row
   const int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
   if (i >= (int64_t)a.K * cpr) return;
   const int k = (int)(i / cpr);
   int col = (int)(i % cpr) * 8, seg = 0;
-  while (col >= a.width[seg]) { col -= a.width[seg]; ++seg; }
-  *reinterpret_cast<u32x4 *>(dst + i * 8) = *reinterpret_cast<const u32x4 *>(a.w[seg] + (int64_t)k * a.width[seg] + col);
+  u32x4 v = {0u, 0u, 0u, 0u};
+  if (col < wtot) {
+    while (col >= a.width[seg]) { col -= a.width[seg]; ++seg; }
+    v = *reinterpret_cast<const u32x4 *>(a.w[seg] + (int64_t)k * a.width[seg] + col);
+  }
+  *reinterpret_cast<u32x4 *>(dst + i * 8) = v;
 }
 
 template <class T, int DH>
-__global__ __launch_bounds__(T::NT) void proj_packed_kernel(ProjArgs a, const bf16 *wpack) {
+__global__ __launch_bounds__(T::NT) void proj_packed_kernel(ProjArgs a, const bf16 *wpack, int wpad) {
   static_assert(T::TM == 4 && T::TN == 4 && (DH == 64 || DH == 128), "tile");
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const int b1 = a.width[0], b2 = b1 + a.width[1], b3 = b2 + a.width[2], wtot = b3 + a.width[3];
   int mt, nt;
-  tile_of_block(wtot / T::BN, (a.M + T::BM - 1) / T::BM, mt, nt);
+  tile_of_block(wpad / T::BN, (a.M + T::BM - 1) / T::BM, mt, nt);
   const int m0 = mt * T::BM, n0 = nt * T::BN;
   f32x16 acc[T::TN][T::TM];
   zero_acc<T>(acc);
   {
-    const unsigned boff = (unsigned)((threadIdx.x / (T::BN / 8)) * wtot + (threadIdx.x % (T::BN / 8)) * 8) * 2u;
+    const unsigned boff = (unsigned)((threadIdx.x / (T::BN / 8)) * wpad + (threadIdx.x % (T::BN / 8)) * 8) * 2u;
     PipeStage<T> t0, t1;
-    gemm_mainloop_pipe<T>(a.x + (int64_t)m0 * a.lda, a.lda, a.M - m0, wpack + n0, boff, wtot, a.K, smem, acc, t0, t1,
+    gemm_mainloop_pipe<T>(a.x + (int64_t)m0 * a.lda, a.lda, a.M - m0, wpack + n0, boff, wpad, a.K, smem, acc, t0, t1,
                           NoTail{});
   }
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -587,6 +593,7 @@ __global__ __launch_bounds__(T::NT) void proj_packed_kernel(ProjArgs a, const bf
   __syncthreads();
   // a thread stores the same 16-byte chunk column of every row: its destination is fixed
   const int gcol = n0 + (threadIdx.x & 31) * 8;
+  if (gcol >= wtot) return;        // zero padding of the packed row; no barrier follows
   const int seg = (gcol >= b1) + (gcol >= b2) + (gcol >= b3);
   const int lcol = gcol - (seg == 0 ? 0 : seg == 1 ? b1 : seg == 2 ? b2 : b3);
   const int width = a.width[seg];
@@ -931,8 +938,9 @@ static bool proj_packed_ok(const Dims &d) {
   if (d.dh != 64 && d.dh != 128) return false;
   if (d.wq_w % d.dh || d.wk_w % d.dh || d.wc_w % 64 || d.wg_w % 64 || d.wq_w % 64 || d.wk_w % 64) return false;
   if (d.dh == 128 && (d.wq_w % 128 || d.wk_w % 128 || d.wc_w % 128)) return false;   // head inside one wave tile
-  return d.wtot % 256 == 0 && d.H % 128 == 0 && d.H >= 256;
+  return d.H % 128 == 0 && d.H >= 256;
 }
+static int proj_packed_width(const Dims &d) { return (d.wtot + 255) / 256 * 256; }
 static bool proj_direct_ok(const Dims &d) {
   // RoPE pairing is lane-local only if a wave tile (128 columns) holds whole heads
   if (d.dh != 128) return false;
@@ -953,7 +961,7 @@ bool gemm_shapes_supported(const Dims &d) {
 }
 
 size_t proj_packed_bytes(const Dims &d) {
-  return d.dtype == GTA_BF16 && !proj_direct_big(d) && proj_packed_ok(d) ? (size_t)d.H * d.wtot * 2 : 0;
+  return d.dtype == GTA_BF16 && !proj_direct_big(d) && proj_packed_ok(d) ? (size_t)d.H * proj_packed_width(d) * 2 : 0;
 }
 
 void launch_proj_gemm(const Dims &d, const gta_weights &w, const void *x, int M, const PrefillWs &ws,
@@ -976,9 +984,10 @@ void launch_proj_gemm(const Dims &d, const gta_weights &w, const void *x, int M,
     launch<TileBig>(proj_gemm_kernel<TileBig>, a, nt, st);
   } else if (proj_packed_ok(d)) {
     bf16 *wpack = (bf16 *)ws.wpack;
-    const int64_t chunks = (int64_t)d.H * (d.wtot / 8);
-    pack_weights_kernel<<<(unsigned)((chunks + 255) / 256), 256, 0, st>>>(a, d.wtot, wpack);
-    const int nt = (d.wtot / 256) * ((M + 255) / 256);
+    const int wpad = proj_packed_width(d);
+    const int64_t chunks = (int64_t)d.H * (wpad / 8);
+    pack_weights_kernel<<<(unsigned)((chunks + 255) / 256), 256, 0, st>>>(a, d.wtot, wpad, wpack);
+    const int nt = (wpad / 256) * ((M + 255) / 256);
     static bool attr_set[2] = {false, false};
     const int which = d.dh == 64 ? 0 : 1;
     const void *fn = which == 0 ? (const void *)proj_packed_kernel<TileBig, 64> : (const void *)proj_packed_kernel<TileBig, 128>;
@@ -986,8 +995,8 @@ void launch_proj_gemm(const Dims &d, const gta_weights &w, const void *x, int M,
       (void)hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, TileBig::SMEM);
       attr_set[which] = true;
     }
-    if (which == 0) proj_packed_kernel<TileBig, 64><<<nt, TileBig::NT, TileBig::SMEM, st>>>(a, wpack);
-    else proj_packed_kernel<TileBig, 128><<<nt, TileBig::NT, TileBig::SMEM, st>>>(a, wpack);
+    if (which == 0) proj_packed_kernel<TileBig, 64><<<nt, TileBig::NT, TileBig::SMEM, st>>>(a, wpack, wpad);
+    else proj_packed_kernel<TileBig, 128><<<nt, TileBig::NT, TileBig::SMEM, st>>>(a, wpack, wpad);
   } else {
     const int nt = (d.wtot / 128) * ((M + 255) / 256);
     launch<TileHead>(proj_gemm_kernel<TileHead>, a, nt, st);

@@ -171,14 +171,23 @@ def test_tuned_decode_batches_that_do_not_fill_the_last_workgroup(shape, batch):
 
 
 @pytest.mark.parametrize("shape,with_wo", [("1b", False), ("1b", True), ("wide", False), ("paper", False),
-                                           ("paper", True), ("packed128", False), ("slim", False)])
+                                           ("paper", True), ("packed128", False), ("slim", False),
+                                           ("paper_nq3", True), ("paper_nq6", False), ("paper_nc2", False)])
 def test_tuned_prefill_ragged_small(shape, with_wo):
     """The MFMA prefill path (1B and wide shapes, the paper's own layer shape with heads of 64 and one
     shared key, and a shape with heads of 128 whose tiles straddle the Q | K | C | gate boundaries) on
     short ragged sequences spanning several tiles and tails, every output element and every cached row
-    against the oracle."""
+    against the oracle.  The last three are the paper's smaller layer shapes, whose summed projection
+    width is not a multiple of the 256-column tile (zero-padded packed weights), one of them with two
+    latent groups."""
     if shape == "paper":
         base = W.PAPER_WORKLOADS[0]
+    elif shape == "paper_nq3":   # 12 heads of 64 in 3 groups: width 192 + 64 + 128 + 768
+        base = W.scaled(W.PAPER_WORKLOADS[0], d_model=768, n_heads=12, n_qgroups=3)
+    elif shape == "paper_nq6":   # two heads per group
+        base = W.scaled(W.PAPER_WORKLOADS[0], d_model=768, n_heads=12, n_qgroups=6)
+    elif shape == "paper_nc2":   # 10 groups sharing one key and two latents: width 640 + 64 + 256 + 1280
+        base = W.scaled(W.PAPER_WORKLOADS[0], n_qgroups=10, n_cgroups=2)
     elif shape == "packed128":
         base = W.scaled(W.WORKLOADS[1], d_model=512, n_heads=4, n_qgroups=2, n_kgroups=1, n_cgroups=1, latent_dim=128)
     elif shape == "slim":   # GQA-like: one map per head, latent as wide as a head, several key / latent groups
