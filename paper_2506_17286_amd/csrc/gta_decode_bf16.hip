@@ -401,11 +401,16 @@ __global__ __launch_bounds__(256, S::OCC) void decode_attn_kernel(DecAttnArgs a,
 // probability-times-latent update are bf16 dot products with fp32 sums (v_dot2_f32_bf16, two rows per
 // instruction), which is what keeps the kernel from being bound by VALU issue.  Streams, waves and
 // splits are merged with the usual log-sum-exp weights.  Same three call modes as the kernel above.
-template <int NQ>
+// NC = 2 is the variant with two latents of 128 per row (a wave load covers 2 latent rows): two
+// streams of four rows a step, each lane accumulating the maps of its own latent.
+template <int NQ, int NC = 1>
 __global__ __launch_bounds__(256) void decode_narrow_kernel(DecAttnArgs a, RopeFreq rf) {
-  constexpr int DH = 64, DL = 128, WQ = NQ * DH, WK = DH, WC = DL, half = DH / 2, R = 8;
+  constexpr int DH = 64, DL = 128, WQ = NQ * DH, WK = DH, WC = NC * DL, half = DH / 2, R = 8;
   constexpr int KROW = WK / 8, CROW = WC / 8;   // 16-byte words per cache row
-  static_assert(WQ / 2 <= 256 && WC <= 256, "prologue mapping");
+  constexpr int QPC = NQ / NC;                  // maps per latent
+  constexpr int NCL = 2 * NC, RPL = R / NCL;    // latent loads per step, rows per latent load
+  static_assert((NC == 1 || NC == 2) && NQ % NC == 0, "one or two latents");
+  static_assert(WQ / 2 <= 512 && WC <= 256, "prologue mapping");
   __shared__ float sm[kWaves][NQ], sl[kWaves][NQ];
   __shared__ float lacc[NQ * DL];
   __shared__ float qs[WQ];                                       // rotated queries * scale * log2(e)
@@ -435,21 +440,22 @@ __global__ __launch_bounds__(256) void decode_narrow_kernel(DecAttnArgs a, RopeF
   const u32x4 *Kp = reinterpret_cast<const u32x4 *>(a.kc + (int64_t)slot * a.max_seq * WK);
   const u32x4 *Cp = reinterpret_cast<const u32x4 *>(a.cc + (int64_t)slot * a.max_seq * WC);
 
-  float m[NQ], l[NQ], acc[NQ][8];
+  float m[NQ], l[NQ], acc[QPC][8];   // a latent-layout lane accumulates the maps of its own latent
 #pragma unroll
-  for (int g = 0; g < NQ; ++g) {
-    m[g] = -INFINITY; l[g] = 0.f;
+  for (int g = 0; g < NQ; ++g) { m[g] = -INFINITY; l[g] = 0.f; }
 #pragma unroll
-    for (int e = 0; e < 8; ++e) acc[g][e] = 0.f;
-  }
+  for (int v = 0; v < QPC; ++v)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[v][e] = 0.f;
   const int nblk = (j1 - j0 + R - 1) / R;   // j1 - j0 may be 0 (only the new row)
-  struct Blk { u32x4 k, c0, c1; };
-  Blk bA, bB, bC, bD;   // four steps (3 KiB each) in flight per wave
+  struct Blk { u32x4 k, c[NCL]; };
+  Blk bA, bB, bC, bD;   // four steps (3 or 5 KiB each) in flight per wave
   auto load = [&](Blk &bk, int blk) {   // rows past the slice re-read its last row; weight 0
     const int jb = j0 + blk * R;
     bk.k = __builtin_nontemporal_load(Kp + (int64_t)min(jb + (lane >> 3), j1 - 1) * KROW + (lane & 7));
-    bk.c0 = __builtin_nontemporal_load(Cp + (int64_t)min(jb + (lane >> 4), j1 - 1) * CROW + (lane & 15));
-    bk.c1 = __builtin_nontemporal_load(Cp + (int64_t)min(jb + 4 + (lane >> 4), j1 - 1) * CROW + (lane & 15));
+#pragma unroll
+    for (int i = 0; i < NCL; ++i)
+      bk.c[i] = __builtin_nontemporal_load(Cp + (int64_t)min(jb + i * RPL + lane / CROW, j1 - 1) * CROW + lane % CROW);
   };
 
   // ---- queries (and the new row) into LDS; the first cache blocks are requested right behind the
@@ -472,12 +478,16 @@ __global__ __launch_bounds__(256) void decode_narrow_kernel(DecAttnArgs a, RopeF
     const float l2 = lo * cs - hi * sn, h2 = hi * cs + lo * sn;
     lo = l2; hi = h2;
   };
-  const bool q_thread = tid < WQ / 2;
-  const int qc0 = (tid / half) * DH + tid % half;   // rotation pair (qc0, qc0 + d_h/2)
-  float q_lo = 0.f, q_hi = 0.f;
-  if (q_thread) {
-    if (a.praw) { q_lo = col_sum(qc0); q_hi = col_sum(qc0 + half); }
-    else { q_lo = a.q_direct[(int64_t)b * WQ + qc0]; q_hi = a.q_direct[(int64_t)b * WQ + qc0 + half]; }
+  constexpr int QPT = (WQ / 2 + 255) / 256;   // rotation pairs (qc0, qc0 + d_h/2) per thread
+  float q_lo[QPT], q_hi[QPT];
+#pragma unroll
+  for (int i = 0; i < QPT; ++i) {
+    const int pi = tid + i * 256, qc0 = (pi / half) * DH + pi % half;
+    q_lo[i] = q_hi[i] = 0.f;
+    if (pi < WQ / 2) {
+      if (a.praw) { q_lo[i] = col_sum(qc0); q_hi[i] = col_sum(qc0 + half); }
+      else { q_lo[i] = a.q_direct[(int64_t)b * WQ + qc0]; q_hi[i] = a.q_direct[(int64_t)b * WQ + qc0 + half]; }
+    }
   }
   __builtin_amdgcn_sched_barrier(0);
   if (wave < nblk) load(bA, wave);
@@ -485,10 +495,14 @@ __global__ __launch_bounds__(256) void decode_narrow_kernel(DecAttnArgs a, RopeF
   if (wave + 2 * kWaves < nblk) load(bC, wave + 2 * kWaves);
   if (wave + 3 * kWaves < nblk) load(bD, wave + 3 * kWaves);
   __builtin_amdgcn_sched_barrier(0);
-  if (q_thread) {
-    if (a.praw) rotate(q_lo, q_hi, tid % half);
-    qs[qc0] = q_lo * a.scale_log2e;
-    qs[qc0 + half] = q_hi * a.scale_log2e;
+#pragma unroll
+  for (int i = 0; i < QPT; ++i) {
+    const int pi = tid + i * 256, qc0 = (pi / half) * DH + pi % half;
+    if (pi < WQ / 2) {
+      if (a.praw) rotate(q_lo[i], q_hi[i], pi % half);
+      qs[qc0] = q_lo[i] * a.scale_log2e;
+      qs[qc0 + half] = q_hi[i] * a.scale_log2e;
+    }
   }
   if (has_new) {   // the new token's key row (rotated) and latent row: LDS for this workgroup, cache for the rest
     bf16 *krow = a.kc + ((int64_t)slot * a.max_seq + old) * WK, *crow = a.cc + ((int64_t)slot * a.max_seq + old) * WC;
@@ -499,8 +513,8 @@ __global__ __launch_bounds__(256) void decode_narrow_kernel(DecAttnArgs a, RopeF
       newrow[tid] = rl; newrow[tid + half] = rh;
       krow[tid] = rl; krow[tid + half] = rh;
     }
-    if (tid >= 64 && tid < 64 + WC) {
-      const int c = tid - 64;
+    const int c = NC == 1 ? tid - 64 : tid;   // one latent: waves 1 and 2, beside the key row's wave
+    if (c >= 0 && c < WC) {
       const bf16 r = (bf16)col_sum(WQ + WK + c);
       newrow[WK + c] = r;
       crow[c] = r;
@@ -522,10 +536,17 @@ __global__ __launch_bounds__(256) void decode_narrow_kernel(DecAttnArgs a, RopeF
       qh[g][w] = t;
     }
   const bf16x2 ones = {(bf16)1.0f, (bf16)1.0f};
-  const int src = (lane >> 4) << 3;   // key-layout lane that holds this latent-layout lane's stream
+  // Key layout: lane l holds row l/8 of the step.  Latent layout: lane l holds rows i*RPL + l/CROW of
+  // the step (i = 0 .. NCL-1), i.e. stream c = l/CROW takes rows c, c+RPL, ..., and the maps of latent
+  // (l%CROW)/16.  One latent: 4 streams of 2 rows a step; two latents: 2 streams of 4 rows a step,
+  // taken as two row pairs (c, c+2) and (c+4, c+6).  src = the key-layout lane on row c that hands
+  // this lane its probabilities: with two latents, the odd lanes of a key row hold the second latent's maps.
+  const int strm = lane / CROW, cgl = (lane % CROW) >> 4;
+  const int src = strm * 8 + cgl;
+  constexpr int PAIR_X = NC == 1 ? 32 : 16;   // lane distance to the other row of a pair (row ^ 4 or row ^ 2)
   auto compute = [&](const Blk &bk, int nv) {
     float corr[NQ];
-    bf16x2 pk[NQ];   // (probability of the stream's first row, of its second row), rounded as the MFMA paths do
+    bf16x2 pk[NQ];   // (probability of this lane's row, of its pair's other row), rounded as the MFMA paths do
     const unsigned kw[4] = {bk.k.x, bk.k.y, bk.k.z, bk.k.w};
     const bool valid = (lane >> 3) < nv;
     bool changed = false;
@@ -536,8 +557,10 @@ __global__ __launch_bounds__(256) void decode_narrow_kernel(DecAttnArgs a, RopeF
       for (int w = 0; w < 4; ++w) sc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, kw[w]), qh[g][w], sc, false);
       sc = group_sum<8>(sc);
       sc = valid ? sc : -INFINITY;
-      const float sc2 = __shfl_xor(sc, 32, 64);              // the stream's other row of this step
-      const float mn = fmaxf(m[g], fmaxf(sc, sc2));
+      const float sc2 = __shfl_xor(sc, PAIR_X, 64);          // the pair's other row
+      float mx = fmaxf(sc, sc2);
+      if constexpr (NC == 2) mx = fmaxf(mx, __shfl_xor(mx, 32, 64));   // the stream's other pair
+      const float mn = fmaxf(m[g], mx);
       const float ref = mn > -INFINITY ? mn : 0.f;            // a stream that has seen no row yet
       corr[g] = fast_exp2(m[g] - ref);
       changed |= mn != m[g];
@@ -545,30 +568,44 @@ __global__ __launch_bounds__(256) void decode_narrow_kernel(DecAttnArgs a, RopeF
       t[0] = (bf16)fast_exp2(sc - ref);
       t[1] = (bf16)fast_exp2(sc2 - ref);
       pk[g] = t;
-      l[g] = __builtin_amdgcn_fdot2_f32_bf16(t, ones, l[g] * corr[g], false);   // the sum of the rounded values
+      l[g] = __builtin_amdgcn_fdot2_f32_bf16(t, ones, l[g] * corr[g], false);   // the sum of the rounded values (of this pair)
       m[g] = mn;
     }
-    // latent elements of the step's two rows side by side: word e = (row A's element e, row B's element e)
-    const unsigned ca[4] = {bk.c0.x, bk.c0.y, bk.c0.z, bk.c0.w}, cb[4] = {bk.c1.x, bk.c1.y, bk.c1.z, bk.c1.w};
-    bf16x2 cx[8];
+    // latent elements of a pair's two rows side by side: word e = (row A's element e, row B's element e)
+    bf16x2 cx[NC][8];
 #pragma unroll
-    for (int w = 0; w < 4; ++w) {
-      cx[2 * w] = __builtin_bit_cast(bf16x2, __builtin_amdgcn_perm(cb[w], ca[w], 0x05040100u));
-      cx[2 * w + 1] = __builtin_bit_cast(bf16x2, __builtin_amdgcn_perm(cb[w], ca[w], 0x07060302u));
+    for (int pr = 0; pr < NC; ++pr) {
+      const u32x4 &va = bk.c[2 * pr], &vb = bk.c[2 * pr + 1];
+      const unsigned ca[4] = {va.x, va.y, va.z, va.w}, cb[4] = {vb.x, vb.y, vb.z, vb.w};
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        cx[pr][2 * w] = __builtin_bit_cast(bf16x2, __builtin_amdgcn_perm(cb[w], ca[w], 0x05040100u));
+        cx[pr][2 * w + 1] = __builtin_bit_cast(bf16x2, __builtin_amdgcn_perm(cb[w], ca[w], 0x07060302u));
+      }
     }
     const bool any_changed = __any(changed);
 #pragma unroll
-    for (int g = 0; g < NQ; ++g) {
-      // lane src sits in the key layout on row src/8 = lane/16 (< 4): its pair is (first latent load's
-      // probability, second's)
-      const bf16x2 pp = __builtin_bit_cast(bf16x2, __shfl(__builtin_bit_cast(int, pk[g]), src, 64));
+    for (int v = 0; v < QPC; ++v) {
+      // what this key-layout lane hands out: the odd lanes of a row serve the second latent's maps
+      int give = __builtin_bit_cast(int, pk[v]);
+      float give_corr = corr[v];
+      if constexpr (NC == 2) {
+        if (lane & 1) { give = __builtin_bit_cast(int, pk[QPC + v]); give_corr = corr[QPC + v]; }
+      }
+      // lane src sits in the key layout on the first row of the stream's first pair: its pair is
+      // (first latent load's probability, second's); the second pair's lane is four rows further
+      bf16x2 pp[NC];
+      pp[0] = __builtin_bit_cast(bf16x2, __shfl(give, src, 64));
+      if constexpr (NC == 2) pp[1] = __builtin_bit_cast(bf16x2, __shfl(give, src + 32, 64));
       if (any_changed) {   // wave-uniform
-        const float cr = __shfl(corr[g], src, 64);
+        const float cr = __shfl(give_corr, src, 64);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) acc[g][e] *= cr;
+        for (int e = 0; e < 8; ++e) acc[v][e] *= cr;
       }
 #pragma unroll
-      for (int e = 0; e < 8; ++e) acc[g][e] = __builtin_amdgcn_fdot2_f32_bf16(cx[e], pp, acc[g][e], false);
+      for (int pr = 0; pr < NC; ++pr)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[v][e] = __builtin_amdgcn_fdot2_f32_bf16(cx[pr][e], pp[pr], acc[v][e], false);
     }
   };
   int blk = wave;
@@ -589,31 +626,42 @@ __global__ __launch_bounds__(256) void decode_narrow_kernel(DecAttnArgs a, RopeF
   if (has_new && wave == 0) {   // the new token's own row, from LDS: one more step with a single valid row
     const u32x4 *nr = reinterpret_cast<const u32x4 *>(newrow);
     bA.k = nr[lane & 7];
-    bA.c0 = nr[KROW + (lane & 15)];
-    bA.c1 = bA.c0;
+#pragma unroll
+    for (int i = 0; i < NCL; ++i) bA.c[i] = nr[KROW + lane % CROW];
     compute(bA, 1);
   }
 
-  // ---- merge the four streams of the wave, then the four waves (fixed order), write the partial
+  // ---- merge the streams of the wave, then the four waves (fixed order), write the partial.
+  // One latent: streams 0..3 sit on key rows 0..3 (lanes l, l^8, l^16, l^24); each of a stream's two
+  // key rows holds the stream's whole sum.  Two latents: streams 0 and 1 on rows 0 and 1 (lanes l,
+  // l^8); key rows r and r^4 hold the sums of the stream's two pairs (lanes l, l^32).
   float mw[NQ], lw[NQ];
 #pragma unroll
   for (int g = 0; g < NQ; ++g) {
     float mx = fmaxf(m[g], __shfl_xor(m[g], 8, 64));
-    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+    if constexpr (NC == 1) mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
     const float ref = mx > -INFINITY ? mx : 0.f;
     float lv = l[g] * fast_exp2(m[g] - ref);     // 0 for a stream without rows
     lv += __shfl_xor(lv, 8, 64);
-    lv += __shfl_xor(lv, 16, 64);                // lanes l, l^8, l^16, l^24: one lane group of each stream
-    const float ms = __shfl(m[g], src, 64);      // this latent-layout lane's stream
-    const float sc = fast_exp2(ms - ref);
+    lv += __shfl_xor(lv, NC == 1 ? 16 : 32, 64);
+    mw[g] = mx; lw[g] = lv;
+  }
+#pragma unroll
+  for (int v = 0; v < QPC; ++v) {
+    float give = m[v], mref = mw[v];             // mw is the same in every lane
+    if constexpr (NC == 2) {
+      if (lane & 1) give = m[QPC + v];
+      if (cgl) mref = mw[QPC + v];
+    }
+    const float ms = __shfl(give, src, 64);      // this latent-layout lane's stream and map
+    const float sc = fast_exp2(ms - (mref > -INFINITY ? mref : 0.f));
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      float v = acc[g][e] * sc;
-      v += __shfl_xor(v, 16, 64);
-      v += __shfl_xor(v, 32, 64);
-      acc[g][e] = v;
+      float val = acc[v][e] * sc;
+      if constexpr (NC == 1) val += __shfl_xor(val, 16, 64);
+      val += __shfl_xor(val, 32, 64);
+      acc[v][e] = val;
     }
-    mw[g] = mx; lw[g] = lv;
   }
   if (lane == 0) {
 #pragma unroll
@@ -621,17 +669,19 @@ __global__ __launch_bounds__(256) void decode_narrow_kernel(DecAttnArgs a, RopeF
   }
   __syncthreads();
   for (int w = 0; w < kWaves; ++w) {
-    if (wave == w && lane < 16) {
+    if (wave == w && lane < CROW) {   // lanes of stream 0 hold the wave's sums: latent cgl, elements (lane % 16) * 8 ..
 #pragma unroll
-      for (int g = 0; g < NQ; ++g) {
+      for (int v = 0; v < QPC; ++v) {
+        const int g = cgl * QPC + v;
         float mx = sm[0][g];
 #pragma unroll
         for (int x = 1; x < kWaves; ++x) mx = fmaxf(mx, sm[x][g]);
-        const float ws = mw[g] > -INFINITY ? fast_exp2(mw[g] - mx) : 0.f;
-        float *dst = lacc + g * DL + lane * 8;
+        const float mine = sm[w][g];
+        const float ws = mine > -INFINITY ? fast_exp2(mine - mx) : 0.f;
+        float *dst = lacc + g * DL + (lane & 15) * 8;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-          const float val = acc[g][e] * ws;
+          const float val = acc[v][e] * ws;
           dst[e] = (w == 0) ? val : dst[e] + val;
         }
       }
@@ -1167,9 +1217,11 @@ bool matches(const Dims &d) {
 
 }  // namespace
 
-// one shared key of 64, one latent of 128, 3 / 5 / 6 maps (the paper's 160M, 500M and 1B GTA models)
+// one shared key of 64 and one latent of 128 with 3 / 5 / 6 maps, or two latents with 6 / 10 maps (the
+// paper's 160M, 500M and 1B GTA models)
 static bool narrow_shape(const Dims &d) {
-  return d.dh == 64 && d.nk == 1 && d.nc == 1 && d.dl == 128 && (d.nq == 3 || d.nq == 5 || d.nq == 6);
+  if (d.dh != 64 || d.nk != 1 || d.dl != 128) return false;
+  return (d.nc == 1 && (d.nq == 3 || d.nq == 5 || d.nq == 6)) || (d.nc == 2 && (d.nq == 6 || d.nq == 10));
 }
 
 bool tuned_decode_supported(const Dims &d) {
@@ -1191,6 +1243,8 @@ static DecAttnArgs attn_args(const Dims &d, const gta_cache &cache, const int32_
 static void launch_attn_any(const Dims &d, const DecAttnArgs &a, const RopeFreq &rf, int batch, hipStream_t st) {
   if (matches<Shape1B>(d)) launch_attn<Shape1B>(d, a, rf, batch, st);
   else if (matches<ShapeWide>(d)) launch_attn<ShapeWide>(d, a, rf, batch, st);
+  else if (d.nc == 2 && d.nq == 10) decode_narrow_kernel<10, 2><<<dim3(a.splits, batch), 256, 0, st>>>(a, rf);
+  else if (d.nc == 2) decode_narrow_kernel<6, 2><<<dim3(a.splits, batch), 256, 0, st>>>(a, rf);
   else if (d.nq == 3) decode_narrow_kernel<3><<<dim3(a.splits, batch), 256, 0, st>>>(a, rf);
   else if (d.nq == 5) decode_narrow_kernel<5><<<dim3(a.splits, batch), 256, 0, st>>>(a, rf);
   else decode_narrow_kernel<6><<<dim3(a.splits, batch), 256, 0, st>>>(a, rf);

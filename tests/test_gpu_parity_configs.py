@@ -114,7 +114,7 @@ def test_paper_layer_decode_b64_t2048_bf16():
     _check_decode_workload(W.PAPER_WORKLOADS[1], check_seqs=list(range(64)))
 
 
-@pytest.mark.parametrize("shape", ["1b", "wide", "paper", "paper_nq3", "paper_nq6"])
+@pytest.mark.parametrize("shape", ["1b", "wide", "paper", "paper_nq3", "paper_nq6", "paper_nc2", "paper_nc2_nq6"])
 def test_tuned_decode_ragged_contexts(shape):
     """The streaming decode kernels (wide rows, and the narrow-row kernel of the paper's own layer
     shapes) on ragged context lengths incl. 0, 1, block tails and empty splits, every output element
@@ -125,6 +125,10 @@ def test_tuned_decode_ragged_contexts(shape):
         base = W.scaled(W.PAPER_WORKLOADS[1], d_model=768, n_heads=12, n_qgroups=3)
     elif shape == "paper_nq6":   # its sibling with 6 groups (two heads per group)
         base = W.scaled(W.PAPER_WORKLOADS[1], d_model=768, n_heads=12, n_qgroups=6)
+    elif shape == "paper_nc2":   # 10 maps sharing one key and two latents (two-latent variant of the kernel)
+        base = W.scaled(W.PAPER_WORKLOADS[1], n_qgroups=10, n_cgroups=2)
+    elif shape == "paper_nc2_nq6":
+        base = W.scaled(W.PAPER_WORKLOADS[1], d_model=768, n_heads=12, n_qgroups=6, n_cgroups=2)
     else:
         base = W.WORKLOADS[2] if shape == "1b" else W.scaled(W.WORKLOADS[4], kind="decode", min_seqlen=None)
     ctx = [0, 1, 7, 8, 31, 32, 33, 255, 777, 1500]
@@ -147,11 +151,13 @@ def test_tuned_decode_ragged_contexts(shape):
         assert np.array_equal(cache.seq_lens.cpu().numpy(), sl)
 
 
-@pytest.mark.parametrize("shape,batch", [("1b", 70), ("1b", 37), ("paper", 131)])
+@pytest.mark.parametrize("shape,batch", [("1b", 70), ("1b", 37), ("paper", 131), ("paper_nc2", 33)])
 def test_tuned_decode_batches_that_do_not_fill_the_last_workgroup(shape, batch):
     """Batch sizes that are not multiples of the sequences a tail workgroup takes (8, 4, 2): short ragged
     contexts, every output element against the oracle."""
     base = W.WORKLOADS[2] if shape == "1b" else W.PAPER_WORKLOADS[1]
+    if shape == "paper_nc2":
+        base = W.scaled(base, n_qgroups=10, n_cgroups=2)
     ctx = [(13 * b + 3) % 97 for b in range(batch)]
     wl = W.scaled(base, batch=batch, seqlen=max(ctx))
     rng = W.make_rng(wl)
