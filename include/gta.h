@@ -128,8 +128,9 @@ GTA_API int gta_prefill(const gta_config *cfg, const gta_weights *weights, const
  *   max_chunk   host upper bound of the longest chunk (sizes the launch), <= cache->max_seq
  *   cache       required.  A sequence whose chunk does not fit (seq_lens + T_b > max_seq) or whose slot
  *               is out of range stores nothing, gets zero output rows and status GTA_ERR_CACHE_FULL.
- * Available where gta_uses_tuned_kernels(cfg, GTA_MODE_PREFILL) is 1 and the attention kernel covers
- * the shape (bf16, d_h 64 or 128); otherwise GTA_ERR_UNSUPPORTED.  Workspace: mode PREFILL_CHUNK. */
+ * Runs on the MFMA kernels where gta_uses_tuned_kernels(cfg, GTA_MODE_PREFILL_CHUNK) is 1 (and a
+ * slot's key / latent rows stay below 2 GiB), on the shape-generic kernels otherwise.  Workspace:
+ * mode PREFILL_CHUNK. */
 GTA_API int gta_prefill_chunk(const gta_config *cfg, const gta_weights *weights, const void *x,
                       const int32_t *cu_seqlens, int32_t batch, int64_t total_tokens,
                       int32_t max_chunk, const gta_cache *cache, const int32_t *slots, void *out,

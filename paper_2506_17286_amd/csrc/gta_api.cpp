@@ -2,6 +2,7 @@
 // tuned bf16 kernels or the shape-generic kernels.  No device code in this file.
 #include <math.h>
 
+#include <algorithm>
 #include "gta_internal.h"
 #include "gta_tuned.h"
 
@@ -150,6 +151,7 @@ int gta_uses_tuned_kernels(const gta_config *cfg, int mode) {
   if (rc != GTA_OK) return rc;
   if (mode == GTA_MODE_PREFILL) return tuned_prefill_supported(d) ? 1 : 0;
   if (mode == GTA_MODE_DECODE) return tuned_decode_supported(d) ? 1 : 0;
+  if (mode == GTA_MODE_PREFILL_CHUNK) return tuned_prefill_chunk_supported(d, 1) ? 1 : 0;   // up to the cache-size limit
   return GTA_ERR_DTYPE;
 }
 
@@ -157,8 +159,13 @@ size_t gta_workspace_bytes(const gta_config *cfg, int mode, int32_t batch, int64
                            int32_t num_splits) {
   Dims d;
   if (make_dims(cfg, &d) != GTA_OK || batch <= 0 || max_len < 0) return 0;
-  if (mode == GTA_MODE_PREFILL_CHUNK)
-    return carve_prefill(d, true, true, batch, total_tokens, max_len, nullptr, true).bytes + 256;
+  if (mode == GTA_MODE_PREFILL_CHUNK) {
+    // the call picks the kernels by the cache's capacity too: sized for either choice
+    if (total_tokens < 0) return 0;
+    size_t n = carve_prefill(d, false, true, batch, total_tokens, max_len, nullptr, true).bytes;
+    if (tuned_prefill_supported(d)) n = std::max(n, carve_prefill(d, true, true, batch, total_tokens, max_len, nullptr, true).bytes);
+    return n + 256;
+  }
   if (mode == GTA_MODE_PREFILL) {
     if (total_tokens < 0) return 0;
     // sized for a call with W_O (a superset of the call without)
@@ -214,13 +221,16 @@ int gta_prefill_chunk(const gta_config *cfg, const gta_weights *weights, const v
   if (misaligned(x) || misaligned(out) || ((uintptr_t)cu_seqlens & 3u) || ((uintptr_t)slots & 3u)) return GTA_ERR_ALIGN;
   if ((rc = check_cache(cache)) != GTA_OK) return rc;
   if (max_chunk > cache->max_seq || (!slots && batch > cache->max_batch)) return GTA_ERR_SHAPE;
-  if (!tuned_prefill_chunk_supported(d, cache->max_seq)) return GTA_ERR_UNSUPPORTED;
   if (total_tokens == 0 || max_chunk == 0) return GTA_OK;
   if (!workspace || misaligned(workspace)) return GTA_ERR_WORKSPACE;
-  PrefillWs ws = carve_prefill(d, true, weights->wo != nullptr, batch, total_tokens, max_chunk, workspace, true);
+  const bool tuned = tuned_prefill_chunk_supported(d, cache->max_seq);
+  PrefillWs ws = carve_prefill(d, tuned, weights->wo != nullptr, batch, total_tokens, max_chunk, workspace, true);
   if (ws.bytes > workspace_bytes) return GTA_ERR_WORKSPACE;
-  return tuned_prefill_chunk(d, *weights, x, cu_seqlens, batch, total_tokens, max_chunk, *cache, slots, out, ws,
-                             (hipStream_t)hip_stream);
+  if (tuned)
+    return tuned_prefill_chunk(d, *weights, x, cu_seqlens, batch, total_tokens, max_chunk, *cache, slots, out, ws,
+                               (hipStream_t)hip_stream);
+  return generic_prefill_chunk(d, *weights, x, cu_seqlens, batch, total_tokens, max_chunk, *cache, slots, out, ws,
+                               (hipStream_t)hip_stream);
 }
 
 int gta_decode(const gta_config *cfg, const gta_weights *weights, const void *x_new, int32_t batch,

@@ -151,11 +151,12 @@ struct CacheView {
 };
 
 // Splits the raw projections into Q | K | C | gate, rotates q and k (App. B.1.1) and stores the
-// key / latent rows into the caches at row = position.
+// key / latent rows into the caches at row = position.  rope_by_token: the RoPE table has one row per
+// packed token (chunked prefill) instead of one per position; a position < 0 marks a skipped sequence.
 template <typename T>
 __global__ void finalize_prefill_kernel(Dims d, const float *praw, const int32_t *seq_id, const int32_t *pos,
                                         const float2 *rope, int max_len, int64_t total, T *Q, T *K, T *C,
-                                        float *G, CacheView cv) {
+                                        float *G, CacheView cv, int rope_by_token = 0) {
   int64_t idx = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
   if (idx >= total * d.wtot) return;
   int64_t t = idx / d.wtot;
@@ -163,9 +164,9 @@ __global__ void finalize_prefill_kernel(Dims d, const float *praw, const int32_t
   float v = praw[idx];
   const int p = pos[t];
   const int qk_w = d.wq_w + d.wk_w;
-  if (col < qk_w && d.rope && p < max_len) {
+  if (col < qk_w && d.rope && (rope_by_token || p < max_len)) {
     int e = col % d.dh, half = d.dh / 2;
-    float2 cs = rope[(int64_t)p * half + (e % half)];
+    float2 cs = rope[(rope_by_token ? t : (int64_t)p) * half + (e % half)];
     if (e < half) v = v * cs.x - praw[idx + half] * cs.y;
     else          v = v * cs.x + praw[idx - half] * cs.y;
   }
@@ -173,7 +174,7 @@ __global__ void finalize_prefill_kernel(Dims d, const float *praw, const int32_t
   if (cv.k) {
     int b = seq_id[t];
     slot = cv.slots ? cv.slots[b] : b;
-    if (slot < 0 || slot >= cv.max_batch || p >= cv.max_seq) slot = -1;
+    if (slot < 0 || slot >= cv.max_batch || p >= cv.max_seq || p < 0) slot = -1;
   }
   if (col < d.wq_w) {
     stf(Q, t * d.wq_w + col, v);
@@ -422,6 +423,44 @@ __global__ __launch_bounds__(256) void attn_prefill_generic_kernel(Dims d, const
   }
 }
 
+// Chunked prefill: token t of sequence b's chunk attends over cache rows 0 .. prefix[b] + t of its
+// slot (the chunk's own rows are already stored there).  A skipped sequence (prefix < 0) gets zeros.
+template <typename T, typename TL>
+__global__ __launch_bounds__(256) void attn_chunk_generic_kernel(Dims d, const T *Q, CacheView cv, const int32_t *prefix,
+                                                                 const int32_t *cu, int per_seq, TL *L) {
+  extern __shared__ float qs[];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int b = blockIdx.z, g = blockIdx.y;
+  const int64_t start = cu ? cu[b] : (int64_t)b * per_seq;
+  const int Tb = cu ? cu[b + 1] - cu[b] : per_seq;
+  const int t = blockIdx.x * 4 + wave;
+  const bool active = t < Tb;
+  const int P = prefix[b];
+  float *qw = qs + wave * d.dh;
+  if (active && P >= 0)
+    for (int e = lane; e < d.dh; e += 64) qw[e] = ldf(Q, (start + t) * d.wq_w + g * d.dh + e) * d.scale;
+  __syncthreads();
+  if (!active) return;
+  TL *Lrow = L + (start + t) * (int64_t)(d.nq * d.dl) + g * d.dl;
+  if (P < 0) {
+    for (int col = lane; col < d.dl; col += 64) stf(Lrow, col, 0.f);
+    return;
+  }
+  const int slot = cv.slots ? cv.slots[b] : b;   // valid: prefix >= 0
+  const T *Kb = (const T *)cv.k + (int64_t)slot * cv.max_seq * d.wk_w + (g / d.qpk) * d.dh;
+  const T *Cb = (const T *)cv.c + (int64_t)slot * cv.max_seq * d.wc_w + (g / d.qpc) * d.dl;
+  for (int c0 = 0; c0 < d.dl; c0 += 64 * kNAcc) {
+    float m = -INFINITY, l = 0.f, acc[kNAcc] = {};
+    wave_attend<T, kNAcc>(qw, Kb, d.wk_w, Cb, d.wc_w, 0, P + t + 1, d.dh, c0, d.dl, lane, m, l, acc);
+    const float inv = 1.0f / l;
+#pragma unroll
+    for (int i = 0; i < kNAcc; ++i) {
+      int col = lane + 64 * i;
+      if (c0 + col < d.dl) stf(Lrow + c0, col, acc[i] * inv);
+    }
+  }
+}
+
 // Split-K decode: block (split, group, sequence) = one wave; un-normalised partial (acc, m, l).
 template <typename T>
 __global__ __launch_bounds__(64) void attn_decode_generic_kernel(Dims d, const float *Q, const int32_t *oldlen,
@@ -628,6 +667,44 @@ int prefill_impl(const Dims &d, const gta_weights &w, const T *x, const int32_t 
   return check_launch();
 }
 
+// Chunked prefill on the shape-generic kernels: same steps as prefill_impl with positions behind the
+// cached rows, keys and latents read back from the caches.
+template <typename T>
+int prefill_chunk_impl(const Dims &d, const gta_weights &w, const T *x, const int32_t *cu, int batch, int64_t total,
+                       int max_chunk, const gta_cache &cache, const int32_t *slots, T *out, const PrefillWs &ws,
+                       hipStream_t st) {
+  const int per_seq = (int)(total / batch);
+  const int M = (int)total;
+  launch_prefill_chunk_setup(d, cu, batch, total, ws.seq_id, ws.pos, ws.rope, ws.prefix, cache, slots, st);
+  const T *wmat[4] = {(const T *)w.wq, (const T *)w.wk, (const T *)w.wc, (const T *)w.wg};
+  const int wn[4] = {d.wq_w, d.wk_w, d.wc_w, d.wg_w};
+  int off = 0;
+  for (int i = 0; i < 4; ++i) {
+    launch_gemm(x, (int64_t)d.H, 0, 1, wmat[i], (int64_t)wn[i], 0, M, wn[i], d.H, 1,
+                EpiStoreF32{ws.praw, d.wtot, off}, st);
+    off += wn[i];
+  }
+  CacheView cv = view_of(&cache, slots);
+  finalize_prefill_kernel<T><<<grid1d(total * d.wtot), 256, 0, st>>>(
+      d, ws.praw, ws.seq_id, ws.pos, ws.rope, max_chunk, total, (T *)ws.q, (T *)ws.k, (T *)ws.c, (float *)ws.g, cv, 1);
+  dim3 agrid((max_chunk + 3) / 4, d.nq, batch);
+  attn_chunk_generic_kernel<T, float><<<agrid, 256, 4 * d.dh * sizeof(float), st>>>(
+      d, (const T *)ws.q, cv, ws.prefix, cu, per_seq, (float *)ws.l);
+  const float *L = (const float *)ws.l;
+  if (w.wo) {
+    float *O = (float *)ws.o;
+    launch_gemm(L, (int64_t)d.nq * d.dl, (int64_t)d.dl, d.hpq, (const T *)w.wp, (int64_t)d.dh, (int64_t)d.dl * d.dh,
+                M, d.dh, d.dl, d.nh, EpiGate<float>{O, d.wg_w, (const float *)ws.g, d.wg_w, d.dh, d.gate}, st);
+    launch_gemm(O, (int64_t)d.wg_w, 0, 1, (const T *)w.wo, (int64_t)d.H, 0, M, d.H, d.wg_w, 1,
+                EpiStoreT<T>{out, d.H}, st);
+  } else {
+    launch_gemm(L, (int64_t)d.nq * d.dl, (int64_t)d.dl, d.hpq, (const T *)w.wp, (int64_t)d.dh, (int64_t)d.dl * d.dh,
+                M, d.dh, d.dl, d.nh, EpiGate<T>{out, d.wg_w, (const float *)ws.g, d.wg_w, d.dh, d.gate}, st);
+  }
+  launch_prefill_chunk_commit(cache, slots, cu, batch, total, ws.prefix, st);
+  return check_launch();
+}
+
 template <typename T>
 void decode_project_impl(const Dims &d, const gta_weights &w, const T *x, int batch, const gta_cache &cache,
                          const int32_t *slots, const DecodeWs &ws, hipStream_t st) {
@@ -721,6 +798,14 @@ int generic_prefill(const Dims &d, const gta_weights &w, const void *x, const in
   if (d.dtype == GTA_BF16)
     return prefill_impl<bf16>(d, w, (const bf16 *)x, cu, batch, total, max_len, cache, slots, (bf16 *)out, ws, st);
   return prefill_impl<float>(d, w, (const float *)x, cu, batch, total, max_len, cache, slots, (float *)out, ws, st);
+}
+
+int generic_prefill_chunk(const Dims &d, const gta_weights &w, const void *x, const int32_t *cu, int batch,
+                          int64_t total, int max_chunk, const gta_cache &cache, const int32_t *slots, void *out,
+                          const PrefillWs &ws, hipStream_t st) {
+  if (d.dtype == GTA_F32)
+    return prefill_chunk_impl<float>(d, w, (const float *)x, cu, batch, total, max_chunk, cache, slots, (float *)out, ws, st);
+  return prefill_chunk_impl<bf16>(d, w, (const bf16 *)x, cu, batch, total, max_chunk, cache, slots, (bf16 *)out, ws, st);
 }
 
 int generic_decode(const Dims &d, const gta_weights &w, const void *x_new, int batch, const gta_cache &cache,

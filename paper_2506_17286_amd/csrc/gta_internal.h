@@ -73,6 +73,9 @@ DecodeWs carve_decode(const Dims &d, bool with_wo, int batch, int splits, void *
 int generic_prefill(const Dims &d, const gta_weights &w, const void *x, const int32_t *cu,
                     int batch, int64_t total, int max_len, const gta_cache *cache,
                     const int32_t *slots, void *out, const PrefillWs &ws, hipStream_t st);
+int generic_prefill_chunk(const Dims &d, const gta_weights &w, const void *x, const int32_t *cu, int batch,
+                          int64_t total, int max_chunk, const gta_cache &cache, const int32_t *slots, void *out,
+                          const PrefillWs &ws, hipStream_t st);
 int generic_decode(const Dims &d, const gta_weights &w, const void *x_new, int batch,
                    const gta_cache &cache, const int32_t *slots, void *out, const DecodeWs &ws,
                    hipStream_t st);

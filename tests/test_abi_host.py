@@ -92,8 +92,10 @@ def test_null_and_misaligned_arguments_are_rejected_on_the_host():
     assert rc == B.GTA_ERR_NULL                        # chunked prefill needs a cache
     rc = lib.gta_prefill_chunk(ctypes.byref(cfg), ctypes.byref(w), fake, None, 1, 128, 128, ctypes.byref(cache), None, fake, fake, 1 << 30, None)
     assert rc == B.GTA_ERR_SHAPE                       # chunk longer than the cache rows
-    rc = lib.gta_prefill_chunk(ctypes.byref(cfg), ctypes.byref(w), fake, None, 1, 16, 16, ctypes.byref(cache), None, fake, fake, 1 << 30, None)
-    assert rc == B.GTA_ERR_UNSUPPORTED                 # fp32: no MFMA attention kernel for this configuration
+    rc = lib.gta_prefill_chunk(ctypes.byref(cfg), ctypes.byref(w), fake, None, 1, 16, 16, ctypes.byref(cache), None, fake, fake, 16, None)
+    assert rc == B.GTA_ERR_WORKSPACE
+    rc = lib.gta_prefill_chunk(ctypes.byref(cfg), ctypes.byref(w), fake, None, 3, 16, 16, ctypes.byref(cache), None, fake, fake, 1 << 30, None)
+    assert rc == B.GTA_ERR_SHAPE                       # 16 tokens do not split into 3 equal chunks
     rc = lib.gta_decode(ctypes.byref(cfg), ctypes.byref(w), fake, 1, None, None, fake, 0, fake, 1 << 30, None)
     assert rc == B.GTA_ERR_NULL
     rc = lib.gta_decode(ctypes.byref(cfg), ctypes.byref(w), fake, 3, ctypes.byref(cache), None, fake, 0, fake, 1 << 30, None)

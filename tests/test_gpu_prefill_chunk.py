@@ -132,14 +132,43 @@ def test_chunk_that_does_not_fit_is_skipped():
     assert np.all(U.f64(cache.k)[0] == -3.0) and np.all(U.f64(cache.c)[0] == -3.0)
 
 
-def test_chunked_prefill_is_refused_without_the_mfma_kernels():
-    wl = W.WORKLOADS[0]   # fp32: shape-generic path only
+@pytest.mark.parametrize("shape", ["fp32_small", "bf16_odd"])
+def test_chunked_prefill_on_the_shape_generic_kernels(shape):
+    """Configurations the MFMA kernels do not cover (fp32 elements; bf16 with dimensions off the tile
+    grid) take the shape-generic kernels: prefix then chunk, against one oracle pass, plus a chunk that
+    does not fit."""
+    if shape == "fp32_small":
+        base = W.WORKLOADS[0]
+    else:
+        base = W.scaled(W.WORKLOADS[1], d_model=200, n_heads=6, head_dim=24, n_qgroups=3, n_kgroups=3, n_cgroups=1,
+                        latent_dim=40)
+    lens = [45, 17, 33, 20]
+    pre = [13, 0, 32, 5]
+    slots = [2, 0, 3, 1]
+    wl = W.scaled(base, batch=len(lens), seqlen=max(lens), min_seqlen=None)
     cfg = B.config_of(wl)
-    w = W.draw_weights(wl, W.make_rng(wl))
+    assert B.gta_uses_tuned_kernels(cfg, B.GTA_MODE_PREFILL_CHUNK) == 0
+    w, cu, x = _inputs(wl, lens, with_wo=(shape == "bf16_odd"))
     wdev = U.upload_weights(w, wl.dtype)
-    cache = U.DeviceCache(wl, 1, 128)
-    x = torch.zeros((8, wl.d_model), dtype=torch.float32, device="cuda")
-    out = torch.zeros((8, wl.n_heads * wl.head_dim), dtype=torch.float32, device="cuda")
-    ws = B.alloc_workspace(1 << 20)
-    rc = B.gta_prefill_chunk(cfg, B.make_weights(wdev), x, None, 1, 8, 8, cache.struct, None, out, ws, check=False)
-    assert rc == B.GTA_ERR_UNSUPPORTED
+    cache = U.DeviceCache(wl, 4, 48, fill=-3.0)
+    has = [b for b in range(len(lens)) if pre[b] > 0]
+    xp = np.concatenate([x[cu[b]:cu[b] + pre[b]] for b in has])
+    cup = np.concatenate([[0], np.cumsum([pre[b] for b in has])]).astype(np.int32)
+    U.run_prefill(wl, wdev, xp, cup, cache=cache, slots=[slots[b] for b in has])
+    cache.seq_lens[1] = 40   # 40 + 15 > 48: the chunk of sequence 3 does not fit
+    xc = np.concatenate([x[cu[b] + pre[b]:cu[b + 1]] for b in range(len(lens))])
+    cuc = np.concatenate([[0], np.cumsum([lens[b] - pre[b] for b in range(len(lens))])]).astype(np.int32)
+    out = U.f64(U.run_prefill_chunk(wl, wdev, xc, cuc, cache, slots=slots))
+    ref, Kref, Cref = orc.prefill(U.oracle_config(wl), U.oracle_weights(w), x, cu)
+    kc, cc = U.f64(cache.k), U.f64(cache.c)
+    for b, s_ in enumerate(slots):
+        rows = slice(int(cuc[b]), int(cuc[b + 1]))
+        if b == 3:
+            assert np.all(out[rows] == 0.0)
+            continue
+        U.assert_close(out[rows], ref[cu[b] + pre[b]:cu[b + 1]], wl.dtype, f"generic chunked prefill {shape} seq {b}")
+        U.assert_close(kc[s_, :lens[b]], Kref[cu[b]:cu[b + 1]], wl.dtype, "K cache")
+        U.assert_close(cc[s_, :lens[b]], Cref[cu[b]:cu[b + 1]], wl.dtype, "C cache")
+        assert np.all(kc[s_, lens[b]:] == -3.0) and np.all(cc[s_, lens[b]:] == -3.0)
+    assert cache.seq_lens.cpu().tolist() == [17, 40, 45, 33]
+    assert cache.status.cpu().tolist() == [0, B.GTA_ERR_CACHE_FULL, 0, 0]
