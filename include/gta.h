@@ -83,16 +83,32 @@ typedef struct {
   const void *wo;  /* [n_h*d_h, H], or NULL: the output is the concatenated gated heads */
 } gta_weights;
 
-/* Contiguous grouped-key / latent-value caches (Sec. 3.3, App. B.1.3).  Struct host, arrays
- * device.  Slot s holds seq_lens[s] valid tokens in rows 0..seq_lens[s]-1; row p is position p. */
+/* Grouped-key / latent-value caches (Sec. 3.3, App. B.1.3).  Struct host, arrays device.  Slot s
+ * holds seq_lens[s] valid tokens in rows 0..seq_lens[s]-1; row p is position p.
+ * Two layouts:
+ *   contiguous (block_table NULL): k and c are [max_batch, max_seq, width]; the last three fields are
+ *     ignored.
+ *   block table ("paged"): k and c are pools [num_pages, page_size, width]; row p of slot s is row
+ *     p % page_size of page block_table[s * pages_per_slot + p / page_size], and max_seq must equal
+ *     page_size * pages_per_slot.  An entry outside [0, num_pages) means "no page": rows there are
+ *     never written, and a call that would append into them treats the slot as full
+ *     (GTA_ERR_CACHE_FULL in status, length unchanged, zero output rows where the call defines them
+ *     for a full slot).  Rows below seq_lens are expected to have pages; a missing one is read from
+ *     page 0 (never from outside the pools).  Pages must not be shared between slots that a call
+ *     writes.  The streaming decode kernels need a power-of-two page_size >= 16; other sizes run on
+ *     the shape-generic kernels. */
 typedef struct {
-  void    *k;         /* [max_batch, max_seq, n_k*d_h]  keys after RoPE */
-  void    *c;         /* [max_batch, max_seq, n_c*d_l]  latent values (no RoPE) */
+  void    *k;         /* keys after RoPE, width n_k*d_h */
+  void    *c;         /* latent values (no RoPE), width n_c*d_l */
   int32_t *seq_lens;  /* [max_batch] */
   int32_t *status;    /* [max_batch]; kernels write it only to flag a slot (GTA_ERR_CACHE_FULL,
                          GTA_ERR_SHAPE), never to clear it */
   int32_t  max_batch;
   int32_t  max_seq;
+  const int32_t *block_table; /* [max_batch, pages_per_slot] device, or NULL */
+  int32_t  page_size;
+  int32_t  pages_per_slot;
+  int32_t  num_pages;
 } gta_cache;
 
 /* Bytes of device workspace the call described by the arguments needs.

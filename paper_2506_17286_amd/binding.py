@@ -40,7 +40,9 @@ class gta_weights(ctypes.Structure):
 
 class gta_cache(ctypes.Structure):
     _fields_ = [("k", ctypes.c_void_p), ("c", ctypes.c_void_p), ("seq_lens", ctypes.c_void_p),
-                ("status", ctypes.c_void_p), ("max_batch", ctypes.c_int32), ("max_seq", ctypes.c_int32)]
+                ("status", ctypes.c_void_p), ("max_batch", ctypes.c_int32), ("max_seq", ctypes.c_int32),
+                ("block_table", ctypes.c_void_p), ("page_size", ctypes.c_int32),
+                ("pages_per_slot", ctypes.c_int32), ("num_pages", ctypes.c_int32)]
 
 
 class GtaError(RuntimeError):
@@ -137,6 +139,14 @@ def make_weights(w: Dict[str, "object"]) -> gta_weights:
 def make_cache(k, c, seq_lens, status) -> gta_cache:
     """k [slots, max_seq, n_k*d_h], c [slots, max_seq, n_c*d_l], seq_lens/status int32 [slots] (device)."""
     return gta_cache(_ptr(k), _ptr(c), _ptr(seq_lens), _ptr(status), k.shape[0], k.shape[1])
+
+
+def make_paged_cache(k_pool, c_pool, seq_lens, status, block_table) -> gta_cache:
+    """k_pool [num_pages, page_size, n_k*d_h], c_pool [num_pages, page_size, n_c*d_l], block_table int32
+    [slots, pages_per_slot] (device): row p of slot s is row p % page_size of page block_table[s, p // page_size]."""
+    slots, pps = block_table.shape
+    return gta_cache(_ptr(k_pool), _ptr(c_pool), _ptr(seq_lens), _ptr(status), slots, pps * k_pool.shape[1],
+                     _ptr(block_table), k_pool.shape[1], pps, k_pool.shape[0])
 
 
 def _check(rc: int, where: str) -> None:

@@ -119,10 +119,19 @@ static int check_cache(const gta_cache *c) {
   if (c->max_batch <= 0 || c->max_seq <= 0) return GTA_ERR_SHAPE;
   if (misaligned(c->k) || misaligned(c->c) || ((uintptr_t)c->seq_lens & 3u) || ((uintptr_t)c->status & 3u))
     return GTA_ERR_ALIGN;
+  if (c->block_table) {
+    if ((uintptr_t)c->block_table & 3u) return GTA_ERR_ALIGN;
+    if (c->page_size <= 0 || c->pages_per_slot <= 0 || c->num_pages <= 0) return GTA_ERR_SHAPE;
+    if ((int64_t)c->page_size * c->pages_per_slot != c->max_seq) return GTA_ERR_SHAPE;
+  }
   return GTA_OK;
 }
 
 static const int kMaxBatch = 65535;  // grid.y / grid.z limit
+
+static bool decode_is_tuned(const Dims &d, const gta_cache &c) {
+  return tuned_decode_supported(d) && tuned_decode_layout_ok(c);
+}
 
 }  // namespace gta
 
@@ -223,7 +232,7 @@ int gta_prefill_chunk(const gta_config *cfg, const gta_weights *weights, const v
   if (max_chunk > cache->max_seq || (!slots && batch > cache->max_batch)) return GTA_ERR_SHAPE;
   if (total_tokens == 0 || max_chunk == 0) return GTA_OK;
   if (!workspace || misaligned(workspace)) return GTA_ERR_WORKSPACE;
-  const bool tuned = tuned_prefill_chunk_supported(d, cache->max_seq);
+  const bool tuned = tuned_prefill_chunk_supported(d, cache->max_seq) && tuned_chunk_layout_ok(*cache);
   PrefillWs ws = carve_prefill(d, tuned, weights->wo != nullptr, batch, total_tokens, max_chunk, workspace, true);
   if (ws.bytes > workspace_bytes) return GTA_ERR_WORKSPACE;
   if (tuned)
@@ -249,7 +258,7 @@ int gta_decode(const gta_config *cfg, const gta_weights *weights, const void *x_
   DecodeWs ws = carve_decode(d, weights->wo != nullptr, batch, splits, workspace);
   if (ws.bytes > workspace_bytes) return GTA_ERR_WORKSPACE;
   hipStream_t st = (hipStream_t)hip_stream;
-  if (tuned_decode_supported(d)) return tuned_decode(d, *weights, x_new, batch, *cache, slots, out, ws, st);
+  if (decode_is_tuned(d, *cache)) return tuned_decode(d, *weights, x_new, batch, *cache, slots, out, ws, st);
   return generic_decode(d, *weights, x_new, batch, *cache, slots, out, ws, st);
 }
 
@@ -297,7 +306,7 @@ int gta_decode_attention(const gta_config *cfg, const float *q, const gta_cache 
   if (!q) return GTA_ERR_NULL;
   if (misaligned(q)) return GTA_ERR_ALIGN;
   hipStream_t st = (hipStream_t)hip_stream;
-  if (tuned_decode_supported(d)) {
+  if (decode_is_tuned(d, *cache)) {
     tuned_decode_attention(d, q, nullptr, ws.oldlen, *cache, slots, batch, ws.splits, ws.part, st);
   } else {
     launch_cached_len(*cache, slots, batch, ws.oldlen, st);
@@ -316,7 +325,7 @@ int gta_decode_combine(const gta_config *cfg, const gta_cache *cache, const int3
   if (!l_out) return GTA_ERR_NULL;
   if (misaligned(l_out)) return GTA_ERR_ALIGN;
   hipStream_t st = (hipStream_t)hip_stream;
-  if (tuned_decode_supported(d)) tuned_decode_combine(d, ws.part, ws.oldlen, ws.splits, batch, l_out, st);
+  if (decode_is_tuned(d, *cache)) tuned_decode_combine(d, ws.part, ws.oldlen, ws.splits, batch, l_out, st);
   else generic_decode_combine(d, ws.part, ws.oldlen, ws.splits, batch, l_out, st);
   return check_launch();
 }

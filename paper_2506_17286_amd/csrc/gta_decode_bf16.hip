@@ -76,6 +76,7 @@ struct DecAttnArgs {
   const float *praw; int nsum, wtot, batch, rope;   // split-K partials [nsum, batch, wtot]
   int32_t *oldlen_out;          // [batch] or NULL: index of the newest row that took part, or -1 (none / slot full)
   bf16 *kc, *cc; const int32_t *seq_lens, *slots; int max_batch, max_seq;
+  PageMap pm; int ps_shift;     // block-table layout: page_size = 1 << ps_shift, a multiple of the rows of a step
   int splits; float scale_log2e;
   float *pacc, *pml;
 };
@@ -109,7 +110,10 @@ __global__ __launch_bounds__(256, S::OCC) void decode_attn_kernel(DecAttnArgs a,
   // old = index of the newest row that takes part, n = old + 1 rows in all
   int old;
   if (a.oldlen_in) old = a.oldlen_in[b];
-  else if (a.praw) { const int p = slot_ok ? a.seq_lens[slot] : -1; old = (p >= 0 && p < a.max_seq) ? p : -1; }
+  else if (a.praw) {   // a row without a page counts as a full slot
+    const int p = slot_ok ? a.seq_lens[slot] : -1;
+    old = (p >= 0 && p < a.max_seq && cache_row(a.pm, a.max_seq, slot, p) >= 0) ? p : -1;
+  }
   else old = (slot_ok ? min(a.seq_lens[slot], a.max_seq) : 0) - 1;
   if (a.oldlen_out && s == 0 && tid == 0) a.oldlen_out[b] = old;
   if (old < 0 && (a.praw || a.oldlen_in)) {   // slot full: the tail kernel zero-fills this sequence
@@ -127,8 +131,16 @@ __global__ __launch_bounds__(256, S::OCC) void decode_attn_kernel(DecAttnArgs a,
   // streams one row less and attends to the new row from LDS
   const bool has_new = a.praw != nullptr && j0 < j1 && j1 == n;
   if (has_new) j1 -= 1;
-  const u32x4 *Kp = reinterpret_cast<const u32x4 *>(a.kc + (int64_t)slot * a.max_seq * WK) + lane;
-  const u32x4 *Cp = reinterpret_cast<const u32x4 *>(a.cc + (int64_t)slot * a.max_seq * WC) + lane;
+  const u32x4 *Kp = reinterpret_cast<const u32x4 *>(a.kc) + lane;
+  const u32x4 *Cp = reinterpret_cast<const u32x4 *>(a.cc) + lane;
+  // pool row of logical row jb, the first row of a step (a step never straddles a page)
+  auto row0 = [&](int jb) -> int64_t {
+    if (!a.pm.table) return (int64_t)slot * a.max_seq + jb;
+    const int pi = __builtin_amdgcn_readfirstlane(jb >> a.ps_shift);   // wave-uniform: a scalar load
+    int pg = a.pm.table[(int64_t)slot * a.pm.pages_per_slot + pi];
+    pg = (unsigned)pg >= (unsigned)a.pm.num_pages ? 0 : pg;
+    return ((int64_t)pg << a.ps_shift) + (jb & (a.pm.page_size - 1));
+  };
 
   float m[KCH][QPK], l[KCH][QPK];
 #pragma unroll
@@ -148,9 +160,10 @@ __global__ __launch_bounds__(256, S::OCC) void decode_attn_kernel(DecAttnArgs a,
 
   auto load = [&](u32x4 (&kb)[R][KCH], u32x4 (&cb)[R][CCH], int blk) {
     const int jb = j0 + blk * R;
+    const int64_t rb = row0(jb);
 #pragma unroll
     for (int r = 0; r < R; ++r) {
-      const int64_t j = min(jb + r, j1 - 1);   // rows past the slice re-read its last row; weight 0
+      const int64_t j = rb + min(r, j1 - 1 - jb);   // rows past the slice re-read its last row; weight 0
 #pragma unroll
       for (int i = 0; i < KCH; ++i) kb[r][i] = __builtin_nontemporal_load(Kp + j * KROW + i * 64);
 #pragma unroll
@@ -211,7 +224,8 @@ __global__ __launch_bounds__(256, S::OCC) void decode_attn_kernel(DecAttnArgs a,
     qs[c0 + half] = q_hi[i] * a.scale_log2e;
   }
   if (has_new) {   // the new token's key row (rotated) and latent row: LDS for this workgroup, cache for the rest
-    bf16 *krow = a.kc + ((int64_t)slot * a.max_seq + old) * WK, *crow = a.cc + ((int64_t)slot * a.max_seq + old) * WC;
+    const int64_t nr = cache_row(a.pm, a.max_seq, slot, old);   // >= 0: checked where old was set
+    bf16 *krow = a.kc + nr * WK, *crow = a.cc + nr * WC;
     constexpr int KPAIRS = WK / 2 / 256, CCOLS = WC / 256;
     float k_lo[KPAIRS], k_hi[KPAIRS], cv[CCOLS];   // all partial loads of the row are requested together
 #pragma unroll
@@ -424,7 +438,10 @@ __global__ __launch_bounds__(256) void decode_narrow_kernel(DecAttnArgs a, RopeF
   const bool slot_ok = slot >= 0 && slot < a.max_batch;
   int old;   // index of the newest row that takes part
   if (a.oldlen_in) old = a.oldlen_in[b];
-  else if (a.praw) { const int p = slot_ok ? a.seq_lens[slot] : -1; old = (p >= 0 && p < a.max_seq) ? p : -1; }
+  else if (a.praw) {   // a row without a page counts as a full slot
+    const int p = slot_ok ? a.seq_lens[slot] : -1;
+    old = (p >= 0 && p < a.max_seq && cache_row(a.pm, a.max_seq, slot, p) >= 0) ? p : -1;
+  }
   else old = (slot_ok ? min(a.seq_lens[slot], a.max_seq) : 0) - 1;
   if (a.oldlen_out && s == 0 && tid == 0) a.oldlen_out[b] = old;
   if (old < 0 && (a.praw || a.oldlen_in)) {   // slot full: the tail kernel zero-fills this sequence
@@ -437,8 +454,16 @@ __global__ __launch_bounds__(256) void decode_narrow_kernel(DecAttnArgs a, RopeF
   int j1 = s + 1 == splits ? n : min(n, (int)(units * (s + 1) / splits) * R);
   const bool has_new = a.praw != nullptr && j0 < j1 && j1 == n;
   if (has_new) j1 -= 1;
-  const u32x4 *Kp = reinterpret_cast<const u32x4 *>(a.kc + (int64_t)slot * a.max_seq * WK);
-  const u32x4 *Cp = reinterpret_cast<const u32x4 *>(a.cc + (int64_t)slot * a.max_seq * WC);
+  const u32x4 *Kp = reinterpret_cast<const u32x4 *>(a.kc);
+  const u32x4 *Cp = reinterpret_cast<const u32x4 *>(a.cc);
+  // pool row of logical row jb, the first row of a step (a step never straddles a page)
+  auto row0 = [&](int jb) -> int64_t {
+    if (!a.pm.table) return (int64_t)slot * a.max_seq + jb;
+    const int pi = __builtin_amdgcn_readfirstlane(jb >> a.ps_shift);   // wave-uniform: a scalar load
+    int pg = a.pm.table[(int64_t)slot * a.pm.pages_per_slot + pi];
+    pg = (unsigned)pg >= (unsigned)a.pm.num_pages ? 0 : pg;
+    return ((int64_t)pg << a.ps_shift) + (jb & (a.pm.page_size - 1));
+  };
 
   float m[NQ], l[NQ], acc[QPC][8];   // a latent-layout lane accumulates the maps of its own latent
 #pragma unroll
@@ -451,11 +476,12 @@ __global__ __launch_bounds__(256) void decode_narrow_kernel(DecAttnArgs a, RopeF
   struct Blk { u32x4 k, c[NCL]; };
   Blk bA, bB, bC, bD;   // four steps (3 or 5 KiB each) in flight per wave
   auto load = [&](Blk &bk, int blk) {   // rows past the slice re-read its last row; weight 0
-    const int jb = j0 + blk * R;
-    bk.k = __builtin_nontemporal_load(Kp + (int64_t)min(jb + (lane >> 3), j1 - 1) * KROW + (lane & 7));
+    const int jb = j0 + blk * R, last = j1 - 1 - jb;
+    const int64_t rb = row0(jb);
+    bk.k = __builtin_nontemporal_load(Kp + (rb + min(lane >> 3, last)) * KROW + (lane & 7));
 #pragma unroll
     for (int i = 0; i < NCL; ++i)
-      bk.c[i] = __builtin_nontemporal_load(Cp + (int64_t)min(jb + i * RPL + lane / CROW, j1 - 1) * CROW + lane % CROW);
+      bk.c[i] = __builtin_nontemporal_load(Cp + (rb + min(i * RPL + lane / CROW, last)) * CROW + lane % CROW);
   };
 
   // ---- queries (and the new row) into LDS; the first cache blocks are requested right behind the
@@ -505,7 +531,8 @@ __global__ __launch_bounds__(256) void decode_narrow_kernel(DecAttnArgs a, RopeF
     }
   }
   if (has_new) {   // the new token's key row (rotated) and latent row: LDS for this workgroup, cache for the rest
-    bf16 *krow = a.kc + ((int64_t)slot * a.max_seq + old) * WK, *crow = a.cc + ((int64_t)slot * a.max_seq + old) * WC;
+    const int64_t nr = cache_row(a.pm, a.max_seq, slot, old);   // >= 0: checked where old was set
+    bf16 *krow = a.kc + nr * WK, *crow = a.cc + nr * WC;
     if (tid < half) {
       float k_lo = col_sum(WQ + tid), k_hi = col_sum(WQ + tid + half);
       rotate(k_lo, k_hi, tid);
@@ -1229,12 +1256,22 @@ bool tuned_decode_supported(const Dims &d) {
   return matches<Shape1B>(d) || matches<ShapeWide>(d) || narrow_shape(d);
 }
 
+// The streaming kernels take a page per scalar lookup: a step of up to 8 rows must not straddle pages.
+bool tuned_decode_layout_ok(const gta_cache &cache) {
+  if (!cache.block_table) return true;
+  const int ps = cache.page_size;
+  return ps >= 16 && (ps & (ps - 1)) == 0;
+}
+
 static DecAttnArgs attn_args(const Dims &d, const gta_cache &cache, const int32_t *slots, int batch, int splits,
                              float *part) {
   DecAttnArgs a{};
   a.batch = batch; a.wtot = d.wtot; a.rope = d.rope;
   a.kc = (bf16 *)cache.k; a.cc = (bf16 *)cache.c; a.seq_lens = cache.seq_lens; a.slots = slots;
   a.max_batch = cache.max_batch; a.max_seq = cache.max_seq;
+  a.pm = page_map_of(cache);
+  a.ps_shift = 0;
+  while (a.pm.table && (1 << a.ps_shift) < a.pm.page_size) ++a.ps_shift;
   a.splits = splits; a.scale_log2e = d.scale * 1.4426950408889634f;
   a.pacc = part; a.pml = part + (int64_t)batch * splits * d.nq * d.dl;
   return a;

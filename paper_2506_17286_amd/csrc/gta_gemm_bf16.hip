@@ -400,6 +400,7 @@ struct ProjArgs {
   int rope_by_token;                  // chunked prefill: the table has one row per packed token instead
   int dh;
   bf16 *kcache, *ccache; const int32_t *slots; int max_batch, max_seq;   // kcache NULL = no cache write
+  PageMap pm;                                                             // contiguous or block-table rows
 };
 
 template <class T>
@@ -465,7 +466,10 @@ __global__ __launch_bounds__(T::NT) void proj_gemm_kernel(ProjArgs a) {
     if (cache) {
       const int b = a.seq_id[m];
       const int slot = a.slots ? a.slots[b] : b;
-      if (slot >= 0 && slot < a.max_batch && p >= 0 && p < a.max_seq) crow = cache + ((int64_t)slot * a.max_seq + p) * width + nw;
+      if (slot >= 0 && slot < a.max_batch && p >= 0 && p < a.max_seq) {
+        const int64_t cr = cache_row(a.pm, a.max_seq, slot, p);
+        if (cr >= 0) crow = cache + cr * width + nw;
+      }
     }
 #pragma unroll
     for (int tn = 0; tn < T::TN; ++tn)
@@ -489,7 +493,7 @@ __global__ __launch_bounds__(T::NT) void proj_gemm_kernel(ProjArgs a) {
       if (m < a.M) {
         const int p = a.pos[m], b = a.seq_id[m];
         const int slot = a.slots ? a.slots[b] : b;
-        if (slot >= 0 && slot < a.max_batch && p >= 0 && p < a.max_seq) cr = (int64_t)slot * a.max_seq + p;
+        if (slot >= 0 && slot < a.max_batch && p >= 0 && p < a.max_seq) cr = cache_row(a.pm, a.max_seq, slot, p);
       }
       crow_of[threadIdx.x] = cr;
     }
@@ -586,7 +590,7 @@ __global__ __launch_bounds__(T::NT) void proj_packed_kernel(ProjArgs a, const bf
     if (m < a.M) {
       const int p = a.pos[m], b = a.seq_id[m];
       const int slot = a.slots ? a.slots[b] : b;
-      if (slot >= 0 && slot < a.max_batch && p >= 0 && p < a.max_seq) cr = (int64_t)slot * a.max_seq + p;
+      if (slot >= 0 && slot < a.max_batch && p >= 0 && p < a.max_seq) cr = cache_row(a.pm, a.max_seq, slot, p);
     }
     crow_of[threadIdx.x] = cr;
   }
@@ -978,6 +982,7 @@ void launch_proj_gemm(const Dims &d, const gta_weights &w, const void *x, int M,
   if (cache) {
     a.kcache = (bf16 *)cache->k; a.ccache = (bf16 *)cache->c; a.slots = slots;
     a.max_batch = cache->max_batch; a.max_seq = cache->max_seq;
+    a.pm = page_map_of(*cache);
   }
   if (proj_direct_big(d)) {
     const int nt = (d.wtot / 256) * ((M + 255) / 256);

@@ -148,6 +148,7 @@ struct CacheView {
   int32_t *seq_lens, *status;
   const int32_t *slots;
   int max_batch, max_seq;
+  PageMap pm;
 };
 
 // Splits the raw projections into Q | K | C | gate, rotates q and k (App. B.1.1) and stores the
@@ -181,11 +182,13 @@ __global__ void finalize_prefill_kernel(Dims d, const float *praw, const int32_t
   } else if (col < qk_w) {
     int c = col - d.wq_w;
     stf(K, t * d.wk_w + c, v);
-    if (slot >= 0) stf((T *)cv.k, ((int64_t)slot * cv.max_seq + p) * d.wk_w + c, v);
+    const int64_t cr = slot >= 0 ? cache_row(cv.pm, cv.max_seq, slot, p) : -1;
+    if (cr >= 0) stf((T *)cv.k, cr * d.wk_w + c, v);
   } else if (col < qk_w + d.wc_w) {
     int c = col - qk_w;
     stf(C, t * d.wc_w + c, v);
-    if (slot >= 0) stf((T *)cv.c, ((int64_t)slot * cv.max_seq + p) * d.wc_w + c, v);
+    const int64_t cr = slot >= 0 ? cache_row(cv.pm, cv.max_seq, slot, p) : -1;
+    if (cr >= 0) stf((T *)cv.c, cr * d.wc_w + c, v);
   } else {
     G[t * d.wg_w + (col - qk_w - d.wc_w)] = v;
   }
@@ -195,7 +198,7 @@ __device__ __forceinline__ void prefill_commit_seq(const CacheView &cv, const in
   int n = cu ? cu[b + 1] - cu[b] : per_seq;
   int slot = cv.slots ? cv.slots[b] : b;
   if (slot < 0 || slot >= cv.max_batch) return;
-  if (n <= cv.max_seq) cv.seq_lens[slot] = n;
+  if (n <= cv.max_seq && rows_backed(cv.pm, slot, 0, n)) cv.seq_lens[slot] = n;
   else cv.status[slot] = GTA_ERR_CACHE_FULL;
 }
 
@@ -238,7 +241,7 @@ __device__ __forceinline__ int chunk_prefix(const CacheView &cv, const int32_t *
   const int slot = cv.slots ? cv.slots[b] : b;
   if (slot < 0 || slot >= cv.max_batch) return -1;
   const int old = cv.seq_lens[slot], n = cu ? cu[b + 1] - cu[b] : per_seq;
-  return (old >= 0 && old + n <= cv.max_seq) ? old : -1;
+  return (old >= 0 && old + n <= cv.max_seq && rows_backed(cv.pm, slot, old, old + n)) ? old : -1;
 }
 
 __global__ void prefill_chunk_setup_kernel(const int32_t *cu, int batch, int64_t total, int per_seq, int32_t *seq_id,
@@ -304,6 +307,8 @@ __global__ void finalize_decode_kernel(Dims d, const float *praw, int nsum, int 
   bool slot_ok = slot >= 0 && slot < cv.max_batch;
   int p = slot_ok ? cv.seq_lens[slot] : 0;
   bool ok = slot_ok && p >= 0 && p < cv.max_seq;
+  const int64_t cr = ok ? cache_row(cv.pm, cv.max_seq, slot, p) : -1;   // a row without a page: slot full
+  ok = cr >= 0;
   if (col == 0) oldlen[b] = ok ? p : -1;
   if (!ok) return;
   // the projection may arrive as `nsum` split-K partials of [batch, wtot]
@@ -326,9 +331,9 @@ __global__ void finalize_decode_kernel(Dims d, const float *praw, int nsum, int 
   if (col < d.wq_w) {
     Qo[(int64_t)b * d.wq_w + col] = v;
   } else if (col < qk_w) {
-    stf((T *)cv.k, ((int64_t)slot * cv.max_seq + p) * d.wk_w + (col - d.wq_w), v);
+    stf((T *)cv.k, cr * d.wk_w + (col - d.wq_w), v);
   } else if (col < qk_w + d.wc_w) {
-    stf((T *)cv.c, ((int64_t)slot * cv.max_seq + p) * d.wc_w + (col - qk_w), v);
+    stf((T *)cv.c, cr * d.wc_w + (col - qk_w), v);
   } else {
     Go[(int64_t)b * d.wg_w + (col - qk_w - d.wc_w)] = v;
   }
@@ -356,16 +361,17 @@ __global__ void decode_commit_kernel(CacheView cv, const int32_t *oldlen, int ba
 // One wave walks keys [j0, j1) of one (sequence, key group): scores of 64 keys at a time (one key
 // per lane), running max / sum (Sec. 3.3 softmax, evaluated online), and the latent-value
 // accumulation L += p_j C_j (reformulated form of Sec. 3.3) with lane-strided columns.
-template <typename T, int NACC>
+// row_of(j) = row of key / latent j in Kb / Cb (identity for a packed sequence, the page map for a cache).
+template <typename T, int NACC, class RowOf>
 __device__ void wave_attend(const float *qw, const T *Kb, int64_t kstride, const T *Cb, int64_t cstride,
                             int j0, int j1, int dh, int c0, int dl, int lane, float &m, float &l,
-                            float (&acc)[NACC]) {
+                            float (&acc)[NACC], RowOf row_of) {
   for (int jb = j0; jb < j1; jb += 64) {
     const int j = jb + lane;
     const bool valid = j < j1;
     float s = -INFINITY;
     if (valid) {
-      const T *kr = Kb + (int64_t)j * kstride;
+      const T *kr = Kb + row_of(j) * kstride;
       float a = 0.f;
       for (int e = 0; e < dh; ++e) a += qw[e] * ldf(kr, e);
       s = a;
@@ -380,7 +386,7 @@ __device__ void wave_attend(const float *qw, const T *Kb, int64_t kstride, const
     const int cnt = min(64, j1 - jb);
     for (int jj = 0; jj < cnt; ++jj) {
       const float pj = __shfl(p, jj, 64);
-      const T *cr = Cb + (int64_t)(jb + jj) * cstride + c0;
+      const T *cr = Cb + row_of(jb + jj) * cstride + c0;
 #pragma unroll
       for (int i = 0; i < NACC; ++i) {
         int col = lane + 64 * i;
@@ -412,7 +418,8 @@ __global__ __launch_bounds__(256) void attn_prefill_generic_kernel(Dims d, const
   const T *Cb = C + start * d.wc_w + (g / d.qpc) * d.dl;
   for (int c0 = 0; c0 < d.dl; c0 += 64 * kNAcc) {
     float m = -INFINITY, l = 0.f, acc[kNAcc] = {};
-    wave_attend<T, kNAcc>(qw, Kb, d.wk_w, Cb, d.wc_w, 0, t + 1, d.dh, c0, d.dl, lane, m, l, acc);
+    wave_attend<T, kNAcc>(qw, Kb, d.wk_w, Cb, d.wc_w, 0, t + 1, d.dh, c0, d.dl, lane, m, l, acc,
+                          [](int j) { return (int64_t)j; });
     const float inv = 1.0f / l;
     TL *Lr = L + (start + t) * (int64_t)(d.nq * d.dl) + g * d.dl + c0;
 #pragma unroll
@@ -447,11 +454,12 @@ __global__ __launch_bounds__(256) void attn_chunk_generic_kernel(Dims d, const T
     return;
   }
   const int slot = cv.slots ? cv.slots[b] : b;   // valid: prefix >= 0
-  const T *Kb = (const T *)cv.k + (int64_t)slot * cv.max_seq * d.wk_w + (g / d.qpk) * d.dh;
-  const T *Cb = (const T *)cv.c + (int64_t)slot * cv.max_seq * d.wc_w + (g / d.qpc) * d.dl;
+  const T *Kb = (const T *)cv.k + (g / d.qpk) * d.dh;
+  const T *Cb = (const T *)cv.c + (g / d.qpc) * d.dl;
   for (int c0 = 0; c0 < d.dl; c0 += 64 * kNAcc) {
     float m = -INFINITY, l = 0.f, acc[kNAcc] = {};
-    wave_attend<T, kNAcc>(qw, Kb, d.wk_w, Cb, d.wc_w, 0, P + t + 1, d.dh, c0, d.dl, lane, m, l, acc);
+    wave_attend<T, kNAcc>(qw, Kb, d.wk_w, Cb, d.wc_w, 0, P + t + 1, d.dh, c0, d.dl, lane, m, l, acc,
+                          [&](int j) { return cache_row_clamped(cv.pm, cv.max_seq, slot, j); });
     const float inv = 1.0f / l;
 #pragma unroll
     for (int i = 0; i < kNAcc; ++i) {
@@ -471,21 +479,22 @@ __global__ __launch_bounds__(64) void attn_decode_generic_kernel(Dims d, const f
   const int old = oldlen[b];
   float *pr = part + (((int64_t)b * splits + s) * d.nq + g) * (d.dl + 2);
   int j0 = 0, j1 = 0;
-  const T *Kb = nullptr, *Cb = nullptr;
+  const T *Kb = (const T *)cv.k + (g / d.qpk) * d.dh, *Cb = (const T *)cv.c + (g / d.qpc) * d.dl;
+  int slot = 0;
   if (old >= 0) {
     const int n = old + 1;
     const int chunk = (n + splits - 1) / splits;
     j0 = min(n, s * chunk);
     j1 = min(n, j0 + chunk);
-    const int slot = cv.slots ? cv.slots[b] : b;
-    Kb = (const T *)cv.k + (int64_t)slot * cv.max_seq * d.wk_w + (g / d.qpk) * d.dh;
-    Cb = (const T *)cv.c + (int64_t)slot * cv.max_seq * d.wc_w + (g / d.qpc) * d.dl;
+    slot = cv.slots ? cv.slots[b] : b;
     for (int e = lane; e < d.dh; e += 64) qs[e] = Q[(int64_t)b * d.wq_w + g * d.dh + e] * d.scale;
   }
   __syncthreads();
   for (int c0 = 0; c0 < d.dl; c0 += 64 * kNAcc) {
     float m = -INFINITY, l = 0.f, acc[kNAcc] = {};
-    if (j1 > j0) wave_attend<T, kNAcc>(qs, Kb, d.wk_w, Cb, d.wc_w, j0, j1, d.dh, c0, d.dl, lane, m, l, acc);
+    if (j1 > j0)
+      wave_attend<T, kNAcc>(qs, Kb, d.wk_w, Cb, d.wc_w, j0, j1, d.dh, c0, d.dl, lane, m, l, acc,
+                            [&](int j) { return cache_row_clamped(cv.pm, cv.max_seq, slot, j); });
 #pragma unroll
     for (int i = 0; i < kNAcc; ++i) {
       int col = lane + 64 * i;
@@ -546,7 +555,8 @@ __global__ void append_copy_kernel(CacheView cv, const char *k_new, const char *
   if (slot < 0 || slot >= cv.max_batch) return;
   const int p = cv.seq_lens[slot];
   if (p < 0 || (int64_t)p + n > cv.max_seq) return;
-  const int64_t src = (int64_t)cu_new[b] + j, dst = (int64_t)slot * cv.max_seq + p + j;
+  const int64_t src = (int64_t)cu_new[b] + j, dst = cache_row(cv.pm, cv.max_seq, slot, p + j);
+  if (dst < 0) return;   // no page: the commit kernel flags the slot
   copy_row_any(k_new + src * krow_bytes, (char *)cv.k + dst * krow_bytes, krow_bytes);
   copy_row_any(c_new + src * crow_bytes, (char *)cv.c + dst * crow_bytes, crow_bytes);
 }
@@ -559,7 +569,7 @@ __global__ void append_commit_kernel(CacheView cv, const int32_t *cu_new, int ba
   if (slot < 0 || slot >= cv.max_batch || n <= 0) return;
   if (n > max_new) { cv.status[slot] = GTA_ERR_SHAPE; return; }  // caller's bound was wrong: nothing copied
   const int p = cv.seq_lens[slot];
-  if (p < 0 || (int64_t)p + n > cv.max_seq) cv.status[slot] = GTA_ERR_CACHE_FULL;
+  if (p < 0 || (int64_t)p + n > cv.max_seq || !rows_backed(cv.pm, slot, p, p + n)) cv.status[slot] = GTA_ERR_CACHE_FULL;
   else cv.seq_lens[slot] = p + n;
 }
 
@@ -619,6 +629,7 @@ CacheView view_of(const gta_cache *c, const int32_t *slots) {
   if (c) {
     v.k = c->k; v.c = c->c; v.seq_lens = c->seq_lens; v.status = c->status;
     v.max_batch = c->max_batch; v.max_seq = c->max_seq;
+    v.pm = page_map_of(*c);
   }
   v.slots = slots;
   return v;

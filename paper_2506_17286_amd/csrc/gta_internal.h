@@ -39,6 +39,45 @@ __device__ __forceinline__ float gate_factor(int kind, float z) {
 
 static inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 
+// ---- cache row addressing ---------------------------------------------------------------------
+// Contiguous layout (table == NULL): row r of slot s is pool row s * max_seq + r.  Block-table layout:
+// it is row r % page_size of page table[s * pages_per_slot + r / page_size]; an entry outside
+// [0, num_pages) means "no page": such a row is never written and counts as missing capacity.
+struct PageMap {
+  const int32_t *table;
+  int page_size, pages_per_slot, num_pages;
+};
+
+inline PageMap page_map_of(const gta_cache &c) {
+  return PageMap{c.block_table, c.page_size, c.pages_per_slot, c.num_pages};
+}
+
+// Pool row of (slot, row), or -1 where the row has no page.  slot and row are in range.
+__device__ __forceinline__ int64_t cache_row(const PageMap &pm, int max_seq, int slot, int row) {
+  if (!pm.table) return (int64_t)slot * max_seq + row;
+  const int pg = pm.table[(int64_t)slot * pm.pages_per_slot + row / pm.page_size];
+  if (pg < 0 || pg >= pm.num_pages) return -1;
+  return (int64_t)pg * pm.page_size + row % pm.page_size;
+}
+
+// The same for reads: a missing page reads page 0 (never outside the pools; the result is then the
+// caller's problem, rows below seq_lens are expected to have pages).
+__device__ __forceinline__ int64_t cache_row_clamped(const PageMap &pm, int max_seq, int slot, int row) {
+  if (!pm.table) return (int64_t)slot * max_seq + row;
+  int pg = pm.table[(int64_t)slot * pm.pages_per_slot + row / pm.page_size];
+  pg = pg < 0 || pg >= pm.num_pages ? 0 : pg;
+  return (int64_t)pg * pm.page_size + row % pm.page_size;
+}
+
+// Do rows [r0, r1) of a slot all have pages?  (One thread walks the slot's table entries.)
+__device__ __forceinline__ bool rows_backed(const PageMap &pm, int slot, int r0, int r1) {
+  if (!pm.table || r1 <= r0) return true;
+  const int32_t *t = pm.table + (int64_t)slot * pm.pages_per_slot;
+  for (int i = r0 / pm.page_size; i <= (r1 - 1) / pm.page_size; ++i)
+    if (t[i] < 0 || t[i] >= pm.num_pages) return false;
+  return true;
+}
+
 // ---- workspace carve-up (one function per mode so sizing and use cannot disagree) ----------
 struct PrefillWs {
   int32_t *seq_id, *pos;   // [total] sequence index and position of each packed token

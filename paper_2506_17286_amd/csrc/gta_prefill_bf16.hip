@@ -72,6 +72,7 @@ struct AttnArgs {
   // chunk mode (prefix != NULL): k, c are the caches [slot, max_seq, width]; the chunk's own rows are
   // already in them behind the prefix[b] rows cached before (prefix[b] < 0: sequence skipped, zero output)
   const int32_t *prefix, *slots; int max_seq;
+  PageMap pm; int ps_shift;   // cache mode on a block-table layout: page_size = 1 << ps_shift, a multiple of BK
 };
 
 // LDS of the fused value decoder: the normalised 256 x DLW tile (row operand) and the DLW x 256
@@ -143,7 +144,11 @@ __global__ __launch_bounds__(T::NT) void attn_prefill_kernel(AttnArgs a) {
   const int ntiles = (kend + T::BK - 1) / T::BK;
   const int kend_w = qw0 < Tb ? P + min(qw0 + 32, Tb) : 0;   // keys [0, kend_w) are visible to this wave
   int64_t krow0 = start;                                     // first key / latent row of the sequence
-  if (a.prefix) krow0 = (int64_t)(a.slots ? a.slots[b] : b) * a.max_seq;
+  int slot = 0;
+  if (a.prefix) {
+    slot = a.slots ? a.slots[b] : b;
+    krow0 = a.pm.table ? 0 : (int64_t)slot * a.max_seq;      // block table: Kb / Cb are the pools, rows per tile
+  }
   const char *Kb = reinterpret_cast<const char *>(a.k + krow0 * a.wk_w + (g / a.qpk) * T::DH);
   const char *Cb = reinterpret_cast<const char *>(a.c + krow0 * a.wc_w + (g / a.qpc) * a.dl + dlc * T::DLW);
   const unsigned wk2 = a.wk_w * 2, wc2 = a.wc_w * 2;
@@ -173,15 +178,26 @@ __global__ __launch_bounds__(T::NT) void attn_prefill_kernel(AttnArgs a) {
   const bool k_loader = T::K_CHUNKS >= T::NT || tid < T::K_CHUNKS, c_loader = T::C_CHUNKS >= T::NT || tid < T::C_CHUNKS;
   auto gload = [&](int t) {
     const int j0 = t * T::BK;
+    const char *Kt = Kb, *Ct = Cb;
+    int sub = 0;
+    if (a.pm.table) {   // the tile's 32 rows sit in one page: rows relative to the tile's first pool row
+      const int jt = min(j0, (Tk - 1) & ~(T::BK - 1));   // tiles past the sequence re-read its last tile
+      const int pi = __builtin_amdgcn_readfirstlane(jt >> a.ps_shift);
+      int pg = a.pm.table[(int64_t)slot * a.pm.pages_per_slot + pi];
+      pg = (unsigned)pg >= (unsigned)a.pm.num_pages ? 0 : pg;
+      const int64_t prow = ((int64_t)pg << a.ps_shift) + (jt & (a.pm.page_size - 1));
+      Kt = Kb + prow * wk2; Ct = Cb + prow * wc2;
+      sub = jt;
+    }
     if (k_loader) {
-      const unsigned r = min(j0 + k_row, Tk - 1);
-      rk = *reinterpret_cast<const u32x4 *>(Kb + (r * wk2 + k_ch * 16));
+      const unsigned r = min(j0 + k_row, Tk - 1) - sub;
+      rk = *reinterpret_cast<const u32x4 *>(Kt + (r * wk2 + k_ch * 16));
     }
     if (c_loader) {
 #pragma unroll
       for (int i = 0; i < T::C_LOADS; ++i) {
-        const unsigned r = min(j0 + c_row + i * T::C_RPP, Tk - 1);
-        rc[i] = *reinterpret_cast<const u32x4 *>(Cb + (r * wc2 + c_ch * 16));
+        const unsigned r = min(j0 + c_row + i * T::C_RPP, Tk - 1) - sub;
+        rc[i] = *reinterpret_cast<const u32x4 *>(Ct + (r * wc2 + c_ch * 16));
       }
     }
   };
@@ -588,6 +604,9 @@ void launch_attn_chunk_bf16(const Dims &d, const void *q, const gta_cache &cache
                             void *L, const void *wp, const void *gate, void *out, bool fuse, hipStream_t st) {
   AttnArgs a = attn_args(d, q, cache.k, cache.c, cu, batch, total);
   a.prefix = prefix; a.slots = slots; a.max_seq = cache.max_seq;
+  a.pm = page_map_of(cache);
+  a.ps_shift = 0;
+  while (a.pm.table && (1 << a.ps_shift) < a.pm.page_size) ++a.ps_shift;
   a.L = (bf16 *)L;
   if (fuse) {
     a.wp = (const bf16 *)wp; a.gate = d.gate ? (const bf16 *)gate : nullptr; a.out = (bf16 *)out;

@@ -6,6 +6,8 @@ namespace gta {
 
 bool tuned_prefill_supported(const Dims &d);
 bool tuned_decode_supported(const Dims &d);
+bool tuned_decode_layout_ok(const gta_cache &cache);   // block-table layouts the streaming decode kernels take
+bool tuned_chunk_layout_ok(const gta_cache &cache);    // ... and the MFMA attention kernel in cache mode
 
 int tuned_prefill(const Dims &d, const gta_weights &w, const void *x, const int32_t *cu, int batch,
                   int64_t total, int max_len, const gta_cache *cache, const int32_t *slots, void *out,

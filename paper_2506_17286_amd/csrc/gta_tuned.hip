@@ -31,6 +31,13 @@ bool tuned_prefill_chunk_supported(const Dims &d, int max_seq) {
   return tuned_prefill_supported(d) && attn_prefill_supported(d, max_seq);
 }
 
+// a 32-row key tile of the attention kernel must not straddle pages
+bool tuned_chunk_layout_ok(const gta_cache &cache) {
+  if (!cache.block_table) return true;
+  const int ps = cache.page_size;
+  return ps >= 32 && (ps & (ps - 1)) == 0;
+}
+
 // Chunked prefill: App. B.1.3 for several new tokens per sequence.  The projection stores the chunk's
 // key / latent rows behind the cached ones; attention then reads keys and latents from the caches.
 int tuned_prefill_chunk(const Dims &d, const gta_weights &w, const void *x, const int32_t *cu, int batch,

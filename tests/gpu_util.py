@@ -63,6 +63,62 @@ class DeviceCache:
         self.seq_lens = torch.zeros(n_slots, dtype=torch.int32, device="cuda") if seq_lens is None else seq_lens
         self.status = torch.zeros(n_slots, dtype=torch.int32, device="cuda")
         self.struct = B.make_cache(self.k, self.c, self.seq_lens, self.status)
+        self.max_seq = self.k.shape[1]
+
+
+class PagedDeviceCache:
+    """Block-table caches: pools of pages, a table that deals every slot `pages_per_slot` distinct pages
+    in a seeded random order (`missing`: (slot, page index) entries left without a page), and spare pages
+    nobody owns.  `logical()` gathers the pools back into [slots, max_seq, width] arrays."""
+
+    def __init__(self, wl, n_slots, page_size, pages_per_slot, spare_pages=3, seed=0, fill=None, missing=()):
+        dt = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
+        kw, cw = wl.kv_width
+        self.page_size, self.pages_per_slot = page_size, pages_per_slot
+        self.max_seq = page_size * pages_per_slot
+        self.num_pages = n_slots * pages_per_slot + spare_pages
+        perm = np.random.default_rng(seed).permutation(self.num_pages)
+        self.table_np = perm[:n_slots * pages_per_slot].reshape(n_slots, pages_per_slot).astype(np.int32)
+        for (s, i) in missing:
+            self.table_np[s, i] = -1
+        self.k = torch.zeros((self.num_pages, page_size, kw), dtype=dt, device="cuda")
+        self.c = torch.zeros((self.num_pages, page_size, cw), dtype=dt, device="cuda")
+        if fill is not None:
+            self.k.fill_(fill); self.c.fill_(fill)
+        self.table = torch.from_numpy(self.table_np).cuda()
+        self.seq_lens = torch.zeros(n_slots, dtype=torch.int32, device="cuda")
+        self.status = torch.zeros(n_slots, dtype=torch.int32, device="cuda")
+        self.struct = B.make_paged_cache(self.k, self.c, self.seq_lens, self.status, self.table)
+
+    def _index(self):
+        idx = torch.from_numpy(np.maximum(self.table_np, 0).astype(np.int64)).cuda()
+        return idx
+
+    def store(self, k_logical: torch.Tensor, c_logical: torch.Tensor):
+        """Scatter [slots, max_seq, width] tensors into the pages (entries without a page are skipped)."""
+        n_slots = self.table_np.shape[0]
+        kl = k_logical.reshape(n_slots, self.pages_per_slot, self.page_size, -1)
+        cl = c_logical.reshape(n_slots, self.pages_per_slot, self.page_size, -1)
+        for s in range(n_slots):
+            for i in range(self.pages_per_slot):
+                pg = int(self.table_np[s, i])
+                if pg >= 0:
+                    self.k[pg] = kl[s, i]; self.c[pg] = cl[s, i]
+
+    def logical(self):
+        """(k, c) as [slots, max_seq, width] tensors gathered through the table (missing pages read page 0)."""
+        idx = self._index()
+        n_slots = self.table_np.shape[0]
+        k = self.k[idx].reshape(n_slots, self.max_seq, -1)
+        c = self.c[idx].reshape(n_slots, self.max_seq, -1)
+        return k, c
+
+    def spare_untouched(self, fill) -> bool:
+        """True if the pages no slot owns still hold the fill value."""
+        owned = set(int(p) for p in self.table_np.ravel() if p >= 0)
+        spare = [p for p in range(self.num_pages) if p not in owned]
+        idx = torch.tensor(spare, dtype=torch.int64, device="cuda")
+        return bool((self.k[idx] == fill).all() and (self.c[idx] == fill).all())
 
 
 def run_prefill(wl, wdev, x_np, cu_np=None, batch=None, max_seqlen=None, cache: DeviceCache = None,
@@ -99,7 +155,7 @@ def run_decode(wl, wdev, x_np, cache: DeviceCache, slots=None, num_splits=0, gat
     x = B.to_device(x_np, wl.dtype)
     width = wl.d_model if wdev.get("wo") is not None else wl.n_heads * wl.head_dim
     out = torch.full((batch, width), float("nan"), dtype=x.dtype, device="cuda")
-    nbytes = B.gta_workspace_bytes(cfg, B.GTA_MODE_DECODE, batch, 0, cache.k.shape[1], num_splits)
+    nbytes = B.gta_workspace_bytes(cfg, B.GTA_MODE_DECODE, batch, 0, cache.max_seq, num_splits)
     ws = B.alloc_workspace(nbytes)
     sl = None if slots is None else torch.from_numpy(np.asarray(slots, dtype=np.int32)).cuda()
     B.gta_decode(cfg, B.make_weights(wdev), x, batch, cache.struct, sl, out, num_splits, ws)

@@ -27,7 +27,8 @@ def test_library_exports_every_declared_function():
 def test_struct_layouts_match_header():
     assert ctypes.sizeof(B.gta_config) == 12 * 4
     assert ctypes.sizeof(B.gta_weights) == 6 * 8
-    assert ctypes.sizeof(B.gta_cache) == 4 * 8 + 8
+    assert ctypes.sizeof(B.gta_cache) == 4 * 8 + 8 + 8 + 3 * 4 + 4   # ... block_table, three ints, tail padding
+    assert B.gta_cache.block_table.offset == 40 and B.gta_cache.page_size.offset == 48
 
 
 def _cfg(**kw):
@@ -98,6 +99,15 @@ def test_null_and_misaligned_arguments_are_rejected_on_the_host():
     assert rc == B.GTA_ERR_SHAPE                       # 16 tokens do not split into 3 equal chunks
     rc = lib.gta_decode(ctypes.byref(cfg), ctypes.byref(w), fake, 1, None, None, fake, 0, fake, 1 << 30, None)
     assert rc == B.GTA_ERR_NULL
+    paged = B.gta_cache(fake, fake, fake, fake, 2, 64, fake, 16, 3, 8)   # 16 * 3 != 64
+    rc = lib.gta_decode(ctypes.byref(cfg), ctypes.byref(w), fake, 1, ctypes.byref(paged), None, fake, 0, fake, 1 << 30, None)
+    assert rc == B.GTA_ERR_SHAPE
+    paged = B.gta_cache(fake, fake, fake, fake, 2, 64, fake, 16, 4, 0)   # no pages in the pool
+    rc = lib.gta_decode(ctypes.byref(cfg), ctypes.byref(w), fake, 1, ctypes.byref(paged), None, fake, 0, fake, 1 << 30, None)
+    assert rc == B.GTA_ERR_SHAPE
+    paged = B.gta_cache(fake, fake, fake, fake, 2, 64, fake + 2, 16, 4, 8)
+    rc = lib.gta_decode(ctypes.byref(cfg), ctypes.byref(w), fake, 1, ctypes.byref(paged), None, fake, 0, fake, 1 << 30, None)
+    assert rc == B.GTA_ERR_ALIGN
     rc = lib.gta_decode(ctypes.byref(cfg), ctypes.byref(w), fake, 3, ctypes.byref(cache), None, fake, 0, fake, 1 << 30, None)
     assert rc == B.GTA_ERR_SHAPE                       # batch exceeds the cache's slots
     rc = lib.gta_cache_append(ctypes.byref(cfg), ctypes.byref(cache), None, fake, None, fake, 1, 1, None)
