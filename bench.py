@@ -99,7 +99,8 @@ def bench_decode(wl, steps, warmup, want_cpu_baseline):
         st = torch.zeros(wl.batch, dtype=torch.int32, device="cuda")
         caches.append((k, c, seq, st, B.make_cache(k, c, seq, st)))
     out = torch.empty((wl.batch, wl.n_heads * wl.head_dim), dtype=x.dtype, device="cuda")
-    ws = B.alloc_workspace(B.gta_workspace_bytes(cfg, B.GTA_MODE_DECODE, wl.batch, 0, max_seq, 0))
+    ws = B.alloc_workspace(max(B.gta_workspace_bytes(cfg, B.GTA_MODE_DECODE, wl.batch, 0, m, 0)
+                               for m in (max_seq, -(-max_seq // 64) * 64)))
 
     def step(i):
         B.gta_decode(cfg, gw, x, wl.batch, caches[i % 2][4], None, out, 0, ws)
@@ -130,6 +131,27 @@ def bench_decode(wl, steps, warmup, want_cpu_baseline):
                        "us_per_launch": ksec * 1e6, "algorithmic_bytes_per_launch": kbytes}
     if want_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline_decode(wl, w, x_np, caches[0])
+    # the same steps on block-table caches: pages of 64 rows dealt in random order over the pools
+    ps = 64
+    pps = -(-max_seq // ps)
+    del caches
+    paged = []
+    for salt in range(2):
+        k, c = W.make_decode_cache_device(wl, pps * ps, salt=salt)
+        seq = torch.full((wl.batch,), wl.seqlen, dtype=torch.int32, device="cuda")
+        st = torch.zeros(wl.batch, dtype=torch.int32, device="cuda")
+        table = torch.from_numpy(np.random.default_rng(wl.seed + salt).permutation(wl.batch * pps)
+                                 .astype(np.int32).reshape(wl.batch, pps)).cuda()
+        kp, cp = k.view(wl.batch * pps, ps, -1), c.view(wl.batch * pps, ps, -1)
+        paged.append((kp, cp, seq, st, table, B.make_paged_cache(kp, cp, seq, st, table)))
+
+    def paged_step(i):
+        B.gta_decode(cfg, gw, x, wl.batch, paged[i % 2][5], None, out, 0, ws)
+
+    psec = _time_steps(paged_step, steps, warmup)
+    assert all(int(c[3].abs().sum()) == 0 for c in paged), "a paged cache slot overflowed"
+    res["paged"] = {"page_size": ps, "us_per_step": psec * 1e6, "cache_GBps": cache_bytes / psec / 1e9,
+                    "vs_contiguous": sec / psec}
     return res
 
 
@@ -408,6 +430,8 @@ def main():
         line.update({"value": main_res["tflops"], "unit": "TFLOP/s", "ms_per_step": main_res["ms_per_step"],
                      "config": {"workload": main_res["workload"], "value_is": "algorithmic flops / whole gta_prefill call"}})
     line["roofline"] = main_res["roofline"]
+    if "paged" in main_res:
+        line["paged_caches"] = main_res["paged"]
     line["measured_ceilings"] = measured_ceilings()
     if "cpu_baseline" in main_res:
         line["cpu_baseline"] = main_res.pop("cpu_baseline")
