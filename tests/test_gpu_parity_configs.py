@@ -178,7 +178,8 @@ def test_tuned_decode_batches_that_do_not_fill_the_last_workgroup(shape, batch):
 
 @pytest.mark.parametrize("shape,with_wo", [("1b", False), ("1b", True), ("wide", False), ("paper", False),
                                            ("paper", True), ("packed128", False), ("slim", False),
-                                           ("paper_nq3", True), ("paper_nq6", False), ("paper_nc2", False)])
+                                           ("paper_nq3", True), ("paper_nq6", False), ("paper_nc2", False),
+                                           ("packed128_pad", False)])
 def test_tuned_prefill_ragged_small(shape, with_wo):
     """The MFMA prefill path (1B and wide shapes, the paper's own layer shape with heads of 64 and one
     shared key, and a shape with heads of 128 whose tiles straddle the Q | K | C | gate boundaries) on
@@ -196,6 +197,8 @@ def test_tuned_prefill_ragged_small(shape, with_wo):
         base = W.scaled(W.PAPER_WORKLOADS[0], n_qgroups=10, n_cgroups=2)
     elif shape == "packed128":
         base = W.scaled(W.WORKLOADS[1], d_model=512, n_heads=4, n_qgroups=2, n_kgroups=1, n_cgroups=1, latent_dim=128)
+    elif shape == "packed128_pad":   # heads of 128, summed width 768 + 128 + 256 + 768 = 7.5 tiles of 256
+        base = W.scaled(W.WORKLOADS[1], d_model=512, n_heads=6, n_qgroups=6, n_kgroups=1, n_cgroups=1, latent_dim=256)
     elif shape == "slim":   # GQA-like: one map per head, latent as wide as a head, several key / latent groups
         base = W.scaled(W.PAPER_WORKLOADS[0], d_model=512, n_heads=8, n_qgroups=8, n_kgroups=2, n_cgroups=2, latent_dim=64)
     else:
