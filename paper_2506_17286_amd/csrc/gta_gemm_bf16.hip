@@ -915,22 +915,9 @@ typedef GemmTile<256, 256, 64, 2, 2> TileBig;    // wave tile 128 x 128
 typedef GemmTile<256, 128, 64, 4, 1> TileHead;   // one 128-wide head per workgroup, wave tile 64(m) x 128(n)
 typedef GemmTile<256, 64, 64, 4, 1> TileHead64;  // one 64-wide head per workgroup, wave tile 64(m) x 64(n)
 
-// Kernels that take more than 64 KiB of dynamic LDS need the attribute set once; kernels of the same
-// signature share this function's statics, so the ones already done are kept by address.
 template <class T, class K, class Args>
 void launch(K kernel, const Args &a, int ntiles, hipStream_t st) {
-  static const void *done[8] = {};
-  const void *fn = (const void *)kernel;
-  bool seen = false;
-  int free_slot = -1;
-  for (int i = 0; i < 8; ++i) {
-    if (done[i] == fn) seen = true;
-    else if (!done[i] && free_slot < 0) free_slot = i;
-  }
-  if (!seen) {
-    (void)hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, T::SMEM);
-    if (free_slot >= 0) done[free_slot] = fn;
-  }
+  allow_dynamic_lds((const void *)kernel, T::SMEM);
   kernel<<<ntiles, T::NT, T::SMEM, st>>>(a);
 }
 
@@ -993,13 +980,9 @@ void launch_proj_gemm(const Dims &d, const gta_weights &w, const void *x, int M,
     const int64_t chunks = (int64_t)d.H * (wpad / 8);
     pack_weights_kernel<<<(unsigned)((chunks + 255) / 256), 256, 0, st>>>(a, d.wtot, wpad, wpack);
     const int nt = (wpad / 256) * ((M + 255) / 256);
-    static bool attr_set[2] = {false, false};
     const int which = d.dh == 64 ? 0 : 1;
-    const void *fn = which == 0 ? (const void *)proj_packed_kernel<TileBig, 64> : (const void *)proj_packed_kernel<TileBig, 128>;
-    if (!attr_set[which]) {
-      (void)hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, TileBig::SMEM);
-      attr_set[which] = true;
-    }
+    allow_dynamic_lds(which == 0 ? (const void *)proj_packed_kernel<TileBig, 64> : (const void *)proj_packed_kernel<TileBig, 128>,
+                      TileBig::SMEM);
     if (which == 0) proj_packed_kernel<TileBig, 64><<<nt, TileBig::NT, TileBig::SMEM, st>>>(a, wpack, wpad);
     else proj_packed_kernel<TileBig, 128><<<nt, TileBig::NT, TileBig::SMEM, st>>>(a, wpack, wpad);
   } else {

@@ -7,9 +7,27 @@
 #include <stdio.h>
 #include <stdlib.h>
 
+#include <mutex>
+
 #include "gta.h"
 
 namespace gta {
+
+// A kernel that takes more than 64 KiB of dynamic LDS needs the limit raised once per device it runs
+// on (the attribute belongs to the kernel's image on the current device).  Fixed table, no allocation.
+inline void allow_dynamic_lds(const void *fn, int bytes) {
+  struct Entry { const void *fn; int dev; };
+  static Entry seen[256];
+  static int n = 0;
+  static std::mutex mu;
+  int dev = 0;
+  (void)hipGetDevice(&dev);
+  std::lock_guard<std::mutex> lock(mu);
+  for (int i = 0; i < n; ++i)
+    if (seen[i].fn == fn && seen[i].dev == dev) return;
+  (void)hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  if (n < 256) seen[n++] = Entry{fn, dev};   // table full: the attribute is simply set again next time
+}
 
 // Validated, derived view of a gta_config.
 struct Dims {

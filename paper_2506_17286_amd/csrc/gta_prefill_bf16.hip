@@ -548,11 +548,7 @@ void launch_attn(const AttnArgs &a0, const Dims &d, int batch, int max_len, hipS
   a.ndlc = d.dl / T::DLW;
   int smem = T::SMEM;
   if constexpr (FUSE) smem = FusedDecoder<T>::SMEM;
-  static bool attr_set = false;
-  if (!attr_set) {
-    (void)hipFuncSetAttribute((const void *)attn_prefill_kernel<T, FUSE>, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-    attr_set = true;
-  }
+  allow_dynamic_lds((const void *)attn_prefill_kernel<T, FUSE>, smem);
   attn_prefill_kernel<T, FUSE><<<a.n_qtiles * a.ndlc * d.nq * batch, T::NT, smem, st>>>(a);
 }
 
