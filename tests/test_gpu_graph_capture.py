@@ -14,8 +14,9 @@ import gpu_util as U
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("shape", ["1b", "paper"])
-def test_decode_step_replays_from_a_graph(shape):
+@pytest.mark.parametrize("shape,page", [("1b", 0), ("paper", 0), ("1b", 64), ("paper", 16)])
+def test_decode_step_replays_from_a_graph(shape, page):
+    """page > 0: the graphed caches are block-table caches (pages in random order), the eager ones contiguous."""
     base = W.WORKLOADS[2] if shape == "1b" else W.PAPER_WORKLOADS[1]
     ctx = [40, 3, 300, 129]
     wl = W.scaled(base, batch=len(ctx), seqlen=max(ctx))
@@ -24,7 +25,7 @@ def test_decode_step_replays_from_a_graph(shape):
     wdev = U.upload_weights(w, wl.dtype)
     gw = B.make_weights(wdev)
     cfg = B.config_of(wl)
-    max_seq = max(ctx) + 8
+    max_seq = 320
     k_np, c_np = W.draw_cache(wl, rng, wl.batch, max_seq)
 
     def fresh_cache():
@@ -32,6 +33,11 @@ def test_decode_step_replays_from_a_graph(shape):
                              seq_lens=torch.tensor(ctx, dtype=torch.int32).cuda())
 
     eager, graphed = fresh_cache(), fresh_cache()
+    if page:
+        flat = graphed
+        graphed = U.PagedDeviceCache(wl, wl.batch, page, max_seq // page, seed=page)
+        graphed.store(flat.k, flat.c)
+        graphed.seq_lens.copy_(flat.seq_lens)
     xs = [B.to_device(W.draw_hidden(wl, rng, wl.batch), wl.dtype) for _ in range(4)]
     x_in = torch.empty_like(xs[0])          # the graph reads its input from this fixed buffer
     out_g = torch.zeros((wl.batch, wl.n_heads * wl.head_dim), dtype=x_in.dtype, device="cuda")
@@ -60,6 +66,7 @@ def test_decode_step_replays_from_a_graph(shape):
         torch.cuda.synchronize()
         assert torch.equal(out_g, out_e), f"replay {step} differs from the eager step"
         assert graphed.seq_lens.cpu().tolist() == [n + step + 1 for n in ctx]
-        assert torch.equal(graphed.k, eager.k) and torch.equal(graphed.c, eager.c)
+        gk, gc = graphed.logical() if page else (graphed.k, graphed.c)
+        assert torch.equal(gk, eager.k) and torch.equal(gc, eager.c)
         # unrelated eager work between the replays
         _ = (out_e.float() @ out_e.float().T).sum().item()
