@@ -77,11 +77,11 @@ PrefillWs carve_prefill(const Dims &d, bool tuned, bool with_wo, int batch, int6
 }
 
 int choose_splits(const Dims &d, int batch, int max_seq, int requested) {
-  (void)d;
   if (requested > 0) return requested > 1024 ? 1024 : requested;
-  // enough (sequence, split) blocks to put ~2 on every one of the 256 CUs, but no split shorter
-  // than 256 cached rows.
-  int want = (512 + batch - 1) / batch;
+  // enough (sequence, split) blocks to put ~2 on every one of the 256 CUs (one where only one fits), but
+  // no split shorter than 256 cached rows.
+  const int target = tuned_decode_target_workgroups(d);
+  int want = (target + batch - 1) / batch;
   int cap = max_seq / 256;
   if (cap < 1) cap = 1;
   int s = want < cap ? want : cap;

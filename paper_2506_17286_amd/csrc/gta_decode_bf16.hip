@@ -1258,6 +1258,13 @@ bool tuned_decode_supported(const Dims &d) {
   return matches<Shape1B>(d) || matches<ShapeWide>(d) || narrow_shape(d);
 }
 
+// Workgroups the split-K launch should have: two per CU, or one where the kernel's registers let only
+// one workgroup live on a CU (the two-latent narrow kernel: batch 64 x 8 splits ran in two rounds,
+// 82 us per step against 65 us with 4 splits).
+int tuned_decode_target_workgroups(const Dims &d) {
+  return tuned_decode_supported(d) && narrow_shape(d) && d.nc == 2 ? 256 : 512;
+}
+
 // The streaming kernels take a page per scalar lookup: a step of up to 8 rows must not straddle pages.
 bool tuned_decode_layout_ok(const gta_cache &cache) {
   if (!cache.block_table) return true;
