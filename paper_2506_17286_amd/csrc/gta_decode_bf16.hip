@@ -1259,10 +1259,14 @@ bool tuned_decode_supported(const Dims &d) {
 }
 
 // Workgroups the split-K launch should have: two per CU, or one where the kernel's registers let only
-// one workgroup live on a CU (the two-latent narrow kernel: batch 64 x 8 splits ran in two rounds,
-// 82 us per step against 65 us with 4 splits).
+// one workgroup live on a CU and 512 would run in two rounds (the two-latent narrow kernel: batch 64,
+// 82 us per step with 8 splits against 65 us with 4; the 8 x 128 + 1024 kernel: batch 8 at 16K rows,
+// 163 us with 64 splits against 137 us with 32).
 int tuned_decode_target_workgroups(const Dims &d) {
-  return tuned_decode_supported(d) && narrow_shape(d) && d.nc == 2 ? 256 : 512;
+  if (d.dtype != GTA_BF16) return 512;
+  if (matches<ShapeWide>(d) && ShapeWide::OCC == 1) return 256;
+  if (narrow_shape(d) && d.nc == 2) return 256;
+  return 512;
 }
 
 // The streaming kernels take a page per scalar lookup: a step of up to 8 rows must not straddle pages.
