@@ -84,6 +84,7 @@ int choose_splits(const Dims &d, int batch, int max_seq, int requested) {
   int want = (target + batch - 1) / batch;
   int cap = max_seq / 256;
   if (cap < 1) cap = 1;
+  if (tuned_decode_supported(d)) cap = std::min(cap, tuned_decode_max_splits(d, batch));
   int s = want < cap ? want : cap;
   if (s < 1) s = 1;
   if (s > 256) s = 256;

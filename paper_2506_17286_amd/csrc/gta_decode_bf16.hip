@@ -1269,6 +1269,14 @@ int tuned_decode_target_workgroups(const Dims &d) {
   return 512;
 }
 
+// The one-sequence tail kernel holds up to 64 splits; beyond that the general tail takes over, which
+// costs more than the extra splits gain once there are at least 256 workgroups anyway (batch 4 at 32K
+// rows: 67 us per step with 64 splits, 74 us with 128; batch 1 and 2 still gain from 128).
+int tuned_decode_max_splits(const Dims &d, int batch) {
+  const bool one_seq_tail = d.dtype == GTA_BF16 && d.dl == 512 && d.dh == 128 && batch * d.nh / 512 < 2;
+  return one_seq_tail && batch >= 4 ? 64 : 1024;
+}
+
 // The streaming kernels take a page per scalar lookup: a step of up to 8 rows must not straddle pages.
 bool tuned_decode_layout_ok(const gta_cache &cache) {
   if (!cache.block_table) return true;

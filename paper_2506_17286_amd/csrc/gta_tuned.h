@@ -7,6 +7,7 @@ namespace gta {
 bool tuned_prefill_supported(const Dims &d);
 bool tuned_decode_supported(const Dims &d);
 int tuned_decode_target_workgroups(const Dims &d);      // split-K launch size the kernel of this shape wants
+int tuned_decode_max_splits(const Dims &d, int batch);   // most splits the cheapest tail kernel of this call takes
 bool tuned_decode_layout_ok(const gta_cache &cache);   // block-table layouts the streaming decode kernels take
 bool tuned_chunk_layout_ok(const gta_cache &cache);    // ... and the MFMA attention kernel in cache mode
 
