@@ -63,7 +63,9 @@ PrefillWs carve_prefill(const Dims &d, bool tuned, bool with_wo, int batch, int6
   w.pos = cv.take<int32_t>(n * 4);
   // RoPE rows: one per position (fresh prefill) or one per packed token (chunked prefill)
   w.rope = cv.take<float2>(d.rope ? (size_t)(chunk ? total : max_len) * (d.dh / 2) * sizeof(float2) : 0);
-  w.praw = cv.take<float>(tuned ? 0 : n * d.wtot * 4);
+  // generic path: raw projections of every token; tuned path: split-K partials of a short prefill (the
+  // same amount whatever the token count, so that a workspace sized for many tokens also serves few)
+  w.praw = cv.take<float>(tuned ? proj_small_rows_bound(d) * d.wtot * 4 : n * d.wtot * 4);
   w.q = cv.take<void>(n * d.wq_w * es);
   w.k = cv.take<void>(n * d.wk_w * es);
   w.c = cv.take<void>(n * d.wc_w * es);

@@ -31,6 +31,8 @@ void tuned_decode_combine(const Dims &d, const float *part, const int32_t *oldle
 // bf16 MFMA GEMMs (gta_gemm_bf16.hip)
 bool gemm_shapes_supported(const Dims &d);
 size_t proj_packed_bytes(const Dims &d);   // workspace for the packed [H, Wtot] weights, 0 if not used
+int proj_small_ksplit(const Dims &d, int64_t M);   // > 0: M tokens take the short-prefill projection with this split
+size_t proj_small_rows_bound(const Dims &d);       // rows of [.., W_tot] fp32 partials that path needs at most
 void launch_proj_gemm(const Dims &d, const gta_weights &w, const void *x, int M, const PrefillWs &ws,
                       const gta_cache *cache, const int32_t *slots, int max_len, hipStream_t st,
                       bool rope_by_token = false);

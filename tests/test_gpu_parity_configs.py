@@ -180,7 +180,8 @@ def test_tuned_decode_batches_that_do_not_fill_the_last_workgroup(shape, batch):
                                            ("paper", True), ("packed128", False), ("slim", False),
                                            ("paper_nq3", True), ("paper_nq6", False), ("paper_nc2", False),
                                            ("packed128_pad", False)])
-def test_tuned_prefill_ragged_small(shape, with_wo):
+@pytest.mark.parametrize("tokens", ["under_1024", "over_1024"])
+def test_tuned_prefill_ragged_small(shape, with_wo, tokens):
     """The MFMA prefill path (1B and wide shapes, the paper's own layer shape with heads of 64 and one
     shared key, and a shape with heads of 128 whose tiles straddle the Q | K | C | gate boundaries) on
     short ragged sequences spanning several tiles and tails, every output element and every cached row
@@ -203,7 +204,9 @@ def test_tuned_prefill_ragged_small(shape, with_wo):
         base = W.scaled(W.PAPER_WORKLOADS[0], d_model=512, n_heads=8, n_qgroups=8, n_kgroups=2, n_cgroups=2, latent_dim=64)
     else:
         base = W.WORKLOADS[1] if shape == "1b" else W.WORKLOADS[4]
-    lens = [1, 37, 256, 300, 129, 64]
+    # up to 1024 tokens a call takes the short-prefill kernels (split-K projection on 64-row tiles), beyond
+    # that the 256-row tiles: both on the same ragged mix
+    lens = [1, 37, 256, 300, 129, 64] if tokens == "under_1024" else [1, 37, 256, 300, 129, 320]
     wl = W.scaled(base, batch=len(lens), seqlen=max(lens), min_seqlen=None)
     assert B.gta_uses_tuned_kernels(B.config_of(wl), B.GTA_MODE_PREFILL) == 1
     rng = W.make_rng(wl)

@@ -63,6 +63,30 @@ def test_prefix_then_chunk_equals_one_pass(shape, with_wo):
 
 
 @pytest.mark.parametrize("shape", ["1b", "paper"])
+def test_chunk_of_more_than_1024_tokens(shape):
+    """A chunk call beyond the short-prefill limit (256-row projection tiles with per-token RoPE rows):
+    chunks of 1200 and 50 tokens behind 100 and 650 cached rows."""
+    lens, pre = [1300, 700], [100, 650]
+    wl = W.scaled(_base(shape), batch=2, seqlen=1300, min_seqlen=None)
+    w, cu, x = _inputs(wl, lens)
+    wdev = U.upload_weights(w, wl.dtype)
+    cache = U.DeviceCache(wl, 2, 1312, fill=-3.0)
+    xp = np.concatenate([x[cu[b]:cu[b] + pre[b]] for b in range(2)])
+    U.run_prefill(wl, wdev, xp, np.array([0, 100, 750], dtype=np.int32), cache=cache)
+    xc = np.concatenate([x[cu[b] + pre[b]:cu[b + 1]] for b in range(2)])
+    out = U.run_prefill_chunk(wl, wdev, xc, np.array([0, 1200, 1250], dtype=np.int32), cache)
+    ref, Kref, Cref = orc.prefill(U.oracle_config(wl), U.oracle_weights(w), x, cu)
+    ref_rows = np.concatenate([ref[cu[b] + pre[b]:cu[b + 1]] for b in range(2)])
+    U.assert_close(U.f64(out), ref_rows, wl.dtype, f"long chunk {shape}")
+    kc, cc = U.f64(cache.k), U.f64(cache.c)
+    for b in range(2):
+        U.assert_close(kc[b, :lens[b]], Kref[cu[b]:cu[b + 1]], wl.dtype, "K cache")
+        U.assert_close(cc[b, :lens[b]], Cref[cu[b]:cu[b + 1]], wl.dtype, "C cache")
+        assert np.all(kc[b, lens[b]:] == -3.0) and np.all(cc[b, lens[b]:] == -3.0)
+    assert cache.seq_lens.cpu().tolist() == lens
+
+
+@pytest.mark.parametrize("shape", ["1b", "paper"])
 def test_several_chunks_in_a_row(shape):
     """One sequence of 700 tokens fed as chunks of 100, 344 and 256 next to a short one fed as 1, 1, 30."""
     lens = [700, 32]
