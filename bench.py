@@ -407,6 +407,13 @@ def main():
     chk = None
     if args.only in (None, "chunk"):    # second half of every sequence of the prefill workload behind the first
         chk = bench_prefill_chunk(W.by_name("prefill_1b_bf16"), 2048, args.steps, args.warmup)
+    short = None
+    if args.only in (None, "chunk"):    # latency of short prompts: one sequence of 128 / 512 / 1024 tokens, 1B shape
+        short = {}
+        for T in (128, 512, 1024):
+            r = bench_prefill(W.scaled(W.by_name("prefill_1b_bf16"), batch=1, seqlen=T, name=f"prefill_1b_1x{T}"),
+                              args.steps, args.warmup, False)
+            short[f"1x{T}"] = {"us_per_call": r["ms_per_step"] * 1e3, "tflops": r["tflops"]}
     if args.only in (None, "varlen"):   # ragged packed batch, 16 sequences of 512..16384 tokens, wider model
         var = bench_prefill(W.by_name("varlen_prefill_bf16"), min(args.steps, 10), min(args.warmup, 3), False)
     if args.only in (None, "paper"):    # one attention layer of the paper's GTA-1B model (heads of 64, d_l = 128)
@@ -417,7 +424,7 @@ def main():
         pap["attention_vs_gqa"] = bench_attention_comparator(args.steps)
     main_res = dec or pre or dec8 or var or (pap["prefill"] if pap else None)
     if main_res is None:   # --only chunk: the chunked figure alone
-        print(json.dumps({"chunked_prefill": chk}))
+        print(json.dumps({"chunked_prefill": chk, "short_prefill_1b": short}))
         return
     line = {
         "metric": "GTA decode HBM GB/s & us/token @32K ctx; prefill bf16 TFLOP/s (% of peak)",
@@ -446,6 +453,8 @@ def main():
         line["varlen_prefill"] = var
     if chk is not None:
         line["chunked_prefill"] = chk
+    if short is not None:
+        line["short_prefill_1b"] = short
     if pap is not None:
         line["paper_layer_gta1b"] = pap if main_res is not pap["prefill"] else {k: v for k, v in pap.items() if k != "prefill"}
     print(json.dumps(line))
