@@ -59,6 +59,7 @@ struct DecShape {
 };
 
 constexpr int kWaves = 4;
+constexpr int kGemmTailBatch = 256;   // from this many sequences on the tail's decoder runs as a GEMM
 
 // Where the queries, the context lengths and (for a full decode step) the new token's key/latent row
 // come from:
@@ -1188,6 +1189,76 @@ __global__ __launch_bounds__(256) void decode_tail_narrow_kernel(Dims d, const f
 // where the gate pre-activations come from: `nsum` terms at stride `kstride`, row pitch `ld`
 struct GateSrc { const float *g; int nsum; int64_t kstride; int ld; };
 
+// Large batches: the tail as a GEMM.  This kernel prepares its operands in one launch — blocks
+// [0, n_q): log-sum-exp merge of the splits of one (sequence, map group) into the normalised group
+// output, rounded to bf16 like the prefill path's (zero row for a full slot); blocks behind them: the
+// gate pre-activations of the new token summed over the projection's split-K partials, bf16; block
+// (0, b) also does the sequence's bookkeeping.  The value decoder then runs on the MFMA GEMM kernels.
+__global__ __launch_bounds__(256) void decode_combine_gate_kernel(Dims d, const float *__restrict__ pacc,
+                                                                  const float *__restrict__ pml,
+                                                                  const int32_t *__restrict__ oldlen, int splits,
+                                                                  GateSrc gs, bf16 *__restrict__ L, bf16 *__restrict__ G,
+                                                                  int32_t *seq_lens, int32_t *status,
+                                                                  const int32_t *__restrict__ slots, int max_batch) {
+  extern __shared__ float wt[];   // [splits]
+  const int tid = threadIdx.x, lane = tid & 63, b = blockIdx.y;
+  if ((int)blockIdx.x >= d.nq) {   // gate columns, 8 per thread
+    const int col = (((int)blockIdx.x - d.nq) * 256 + tid) * 8;
+    if (col >= d.wg_w) return;
+    float v[8] = {};
+    for (int k = 0; k < gs.nsum; ++k) {
+      const float *p = gs.g + k * gs.kstride + (int64_t)b * gs.ld + col;
+      const float4 x0 = *reinterpret_cast<const float4 *>(p), x1 = *reinterpret_cast<const float4 *>(p + 4);
+      v[0] += x0.x; v[1] += x0.y; v[2] += x0.z; v[3] += x0.w; v[4] += x1.x; v[5] += x1.y; v[6] += x1.z; v[7] += x1.w;
+    }
+    bf16 *o = G + (int64_t)b * d.wg_w + col;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o[e] = (bf16)v[e];
+    return;
+  }
+  const int g = blockIdx.x;
+  if (g == 0 && tid == 0) {
+    const int slot = slots ? slots[b] : b;
+    if (slot >= 0 && slot < max_batch) {
+      if (oldlen[b] >= 0) seq_lens[slot] = oldlen[b] + 1;
+      else status[slot] = GTA_ERR_CACHE_FULL;
+    }
+  }
+  bf16 *Lr = L + ((int64_t)b * d.nq + g) * d.dl;
+  if (oldlen[b] < 0) {
+    for (int c = tid; c < d.dl; c += 256) Lr[c] = (bf16)0.f;
+    return;
+  }
+  const float *pm = pml + ((int64_t)b * splits * d.nq + g) * 2;
+  const int64_t ms = (int64_t)d.nq * 2;
+  if (tid < 64) {   // one wave computes the weights
+    float mx = -INFINITY;
+    for (int s = lane; s < splits; s += 64) mx = fmaxf(mx, pm[s * ms]);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
+    float ls = 0.f;
+    for (int s = lane; s < splits; s += 64) {
+      const float m = pm[s * ms];
+      if (m > -INFINITY) ls += exp2f(m - mx) * pm[s * ms + 1];
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) ls += __shfl_xor(ls, o, 64);
+    const float inv = 1.0f / ls;
+    for (int s = lane; s < splits; s += 64) {
+      const float m = pm[s * ms];
+      wt[s] = m > -INFINITY ? exp2f(m - mx) * inv : 0.f;
+    }
+  }
+  __syncthreads();
+  const int64_t as = (int64_t)d.nq * d.dl;
+  for (int c = tid; c < d.dl; c += 256) {
+    const float *pa = pacc + ((int64_t)b * splits * d.nq + g) * d.dl + c;
+    float a0 = 0.f;
+    for (int s = 0; s < splits; ++s) a0 = fmaf(wt[s], pa[s * as], a0);
+    Lr[c] = (bf16)a0;
+  }
+}
+
 template <typename TO, int ROWS>
 void launch_tail(const Dims &d, const float *pacc, const float *pml, const DecodeWs &ws, int batch, GateSrc gs,
                  const bf16 *wp, TO *out, const gta_cache &cache, const int32_t *slots, hipStream_t st) {
@@ -1347,6 +1418,23 @@ int tuned_decode(const Dims &d, const gta_weights &w, const void *x_new, int bat
   }
   const float *pacc = ws.part;
   const float *pml = ws.part + (int64_t)batch * ws.splits * d.nq * d.dl;
+  // Large batches: the per-row decoder of the tail kernels grows with the batch (32 us at 256 sequences,
+  // 115 us at 1024 on the 1B shape); from 256 sequences on it runs as an MFMA GEMM on bf16 operands
+  // (group outputs and gate pre-activations rounded as in prefill), behind one kernel that prepares them.
+  if (batch >= kGemmTailBatch && gemm_shapes_supported(d) && d.wg_w % 8 == 0) {
+    bf16 *Lb = reinterpret_cast<bf16 *>(ws.l), *Gb = reinterpret_cast<bf16 *>(ws.g);   // fp32-sized buffers, used as bf16
+    const int gate_blocks = d.gate ? (d.wg_w / 8 + 255) / 256 : 0;
+    decode_combine_gate_kernel<<<dim3(d.nq + gate_blocks, batch), 256, ws.splits * sizeof(float), st>>>(
+        d, pacc, pml, ws.oldlen, ws.splits, gs, Lb, Gb, cache.seq_lens, cache.status, slots, cache.max_batch);
+    if (w.wo) {
+      bf16 *Ob = reinterpret_cast<bf16 *>(ws.o);
+      launch_decoder_gemm(d, Lb, w.wp, Gb, Ob, batch, st);
+      launch_plain_gemm(Ob, d.wg_w, batch, d.H, d.wg_w, w.wo, out, st);
+    } else {
+      launch_decoder_gemm(d, Lb, w.wp, Gb, out, batch, st);
+    }
+    return check_launch();
+  }
   if (w.wo) {
     launch_tail_any<float>(d, pacc, pml, ws, batch, gs, (const bf16 *)w.wp, ws.o, cache, slots, st);
     generic_out_proj_f32in(d, w, ws.o, batch, out, st);

@@ -998,6 +998,7 @@ static bool proj_direct_big(const Dims &d) {
 
 bool gemm_shapes_supported(const Dims &d) {
   if (d.dtype != GTA_BF16) return false;
+  if (d.H % 128) return false;   // H is also the output width of the W_O GEMM, tiled in 128 columns
   if (!proj_direct_ok(d) && !proj_packed_ok(d)) return false;
   if (d.dl % 64) return false;
   // row offsets inside a 256-row tile are kept in 32 bits

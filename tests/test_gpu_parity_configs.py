@@ -176,6 +176,40 @@ def test_tuned_decode_batches_that_do_not_fill_the_last_workgroup(shape, batch):
     assert np.array_equal(cache.seq_lens.cpu().numpy(), sl)
 
 
+@pytest.mark.parametrize("shape,batch,with_wo", [("1b", 300, False), ("1b", 257, True), ("paper", 300, False),
+                                                 ("paper", 1100, True), ("wide", 256, False)])
+def test_tuned_decode_large_batches(shape, batch, with_wo):
+    """From 256 sequences on the decode tail runs as a GEMM on bf16 operands (beyond 1024 on the 256-row
+    tiles): short ragged contexts incl. empty ones and a full slot, every output element against the oracle."""
+    if shape == "1b":
+        base = W.WORKLOADS[2]
+    elif shape == "paper":
+        base = W.PAPER_WORKLOADS[1]
+    else:
+        base = W.scaled(W.WORKLOADS[4], kind="decode", min_seqlen=None)
+    ctx = [(7 * b + 3) % 41 for b in range(batch)]
+    max_seq = 41
+    ctx[5] = max_seq          # a full slot: zero output row, status flagged, length unchanged
+    wl = W.scaled(base, batch=batch, seqlen=max_seq)
+    rng = W.make_rng(wl)
+    w = W.draw_weights(wl, rng, with_wo=with_wo)
+    x = W.draw_hidden(wl, rng, batch)
+    k_np, c_np = W.draw_cache(wl, rng, batch, max_seq)
+    wdev = U.upload_weights(w, wl.dtype)
+    cache = U.DeviceCache(wl, batch, max_seq, k=B.to_device(k_np, wl.dtype), c=B.to_device(c_np, wl.dtype),
+                          seq_lens=torch.tensor(ctx, dtype=torch.int32).cuda())
+    out = U.f64(U.run_decode(wl, wdev, x, cache))
+    sl = np.array(ctx, dtype=np.int32); st = np.zeros(batch, dtype=np.int32)
+    ref = orc.decode(U.oracle_config(wl), U.oracle_weights(w), x, k_np.astype(np.float64), c_np.astype(np.float64),
+                     sl, st, list(range(batch)))
+    U.assert_close(out, ref, wl.dtype, f"decode {shape} batch {batch}")
+    assert np.all(out[5] == 0.0) and np.all(ref[5] == 0.0)
+    want = [n + 1 for n in ctx]; want[5] = max_seq
+    assert cache.seq_lens.cpu().tolist() == want
+    stt = cache.status.cpu().tolist()
+    assert stt[5] == B.GTA_ERR_CACHE_FULL and sum(1 for v in stt if v) == 1
+
+
 @pytest.mark.parametrize("shape,with_wo", [("1b", False), ("1b", True), ("wide", False), ("paper", False),
                                            ("paper", True), ("packed128", False), ("slim", False),
                                            ("paper_nq3", True), ("paper_nq6", False), ("paper_nc2", False),
