@@ -1012,19 +1012,29 @@ size_t proj_packed_bytes(const Dims &d) {
 
 static bool skinny_wide_tiles(const Dims &d);
 
-// Short prefill: split-K projection on 64-row tiles plus a finalize kernel, up to 1024 tokens (measured
-// at the 1B shape: 128 tokens 11 us against 55 us on one round of 256-row tiles, 1024 tokens 34 against 61).
+// Short prefill: split-K projection on 64-row tiles plus a finalize kernel, as long as the 256-row tiles
+// would fill at most half of the CUs (and up to 4096 tokens).  Measured, whole calls: 1B shape (20 column
+// tiles) 1280 tokens 125 us against 147 us, 1536 tokens 140 against 158, 3072 tokens 244 against 220;
+// the paper's layer (7 column tiles) 2048 tokens 110 against 127, 4096 tokens equal; the 8 x 128 + 1024
+// shape (28 column tiles) 1500 tokens 256 against 216; the projection alone at the 1B shape: 128 tokens
+// 11 us against 55 us, 1024 tokens 34 against 61.
+static int proj_small_max_tokens(const Dims &d) {
+  const int col_tiles = (d.wtot + 255) / 256;
+  const int m = 128 / col_tiles * 256;
+  return m < 4096 ? m : 4096;
+}
+
 int proj_small_ksplit(const Dims &d, int64_t M) {
-  if (M <= 0 || M > 1024 || !gemm_shapes_supported(d)) return 0;
+  if (!gemm_shapes_supported(d) || M <= 0 || M > proj_small_max_tokens(d)) return 0;
   return skinny_ksplit(d, (int)M);
 }
 
-// Rows of fp32 partials [ksplit * M, W_tot] the short path needs at most, whatever M <= 1024 is:
+// Rows of fp32 partials [ksplit * M, W_tot] the short path needs at most, whatever M is:
 // ksplit <= 768 / tiles + 1 with tiles = n_tiles * ceil(M / 64).
 size_t proj_small_rows_bound(const Dims &d) {
   if (!gemm_shapes_supported(d)) return 0;
   const int ntn = d.wtot / (skinny_wide_tiles(d) ? 128 : 64);
-  return (size_t)(768 * 64 / ntn + 1024);
+  return (size_t)(768 * 64 / ntn + proj_small_max_tokens(d));
 }
 
 void launch_proj_gemm(const Dims &d, const gta_weights &w, const void *x, int M, const PrefillWs &ws,
@@ -1107,7 +1117,7 @@ void launch_decoder_gemm(const Dims &d, const void *L, const void *wp, const voi
   a.L = (const bf16 *)L; a.ldl = (int64_t)d.nq * d.dl; a.M = M;
   a.wp = (const bf16 *)wp; a.dl = d.dl; a.dh = d.dh; a.hpq = d.hpq; a.nh = d.nh;
   a.g = (const bf16 *)g; a.gate = d.gate; a.out = (bf16 *)out;
-  if (M <= 1024 && (d.dh == 64 || d.dh == 128)) {   // short prefill: 64-row tiles, one head (or half of one) each
+  if ((M <= 1024 || proj_small_ksplit(d, M)) && (d.dh == 64 || d.dh == 128)) {   // short prefill: 64-row tiles, one head (or half of one) each
     if (d.dh == 128) launch<TileSkinny64>(decoder_gemm_kernel<TileSkinny64>, a, d.nh * ((M + 63) / 64), st);
     else launch<TileSkinny64N64>(decoder_gemm_kernel<TileSkinny64N64>, a, d.nh * ((M + 63) / 64), st);
     return;

@@ -214,7 +214,7 @@ def test_tuned_decode_large_batches(shape, batch, with_wo):
                                            ("paper", True), ("packed128", False), ("slim", False),
                                            ("paper_nq3", True), ("paper_nq6", False), ("paper_nc2", False),
                                            ("packed128_pad", False)])
-@pytest.mark.parametrize("tokens", ["under_1024", "over_1024"])
+@pytest.mark.parametrize("tokens", ["few", "many"])
 def test_tuned_prefill_ragged_small(shape, with_wo, tokens):
     """The MFMA prefill path (1B and wide shapes, the paper's own layer shape with heads of 64 and one
     shared key, and a shape with heads of 128 whose tiles straddle the Q | K | C | gate boundaries) on
@@ -238,9 +238,13 @@ def test_tuned_prefill_ragged_small(shape, with_wo, tokens):
         base = W.scaled(W.PAPER_WORKLOADS[0], d_model=512, n_heads=8, n_qgroups=8, n_kgroups=2, n_cgroups=2, latent_dim=64)
     else:
         base = W.WORKLOADS[1] if shape == "1b" else W.WORKLOADS[4]
-    # up to 1024 tokens a call takes the short-prefill kernels (split-K projection on 64-row tiles), beyond
-    # that the 256-row tiles: both on the same ragged mix
-    lens = [1, 37, 256, 300, 129, 64] if tokens == "under_1024" else [1, 37, 256, 300, 129, 320]
+    # calls of few tokens take the short-prefill kernels (split-K projection on 64-row tiles; the limit
+    # depends on the shape and is at most 4096 tokens), longer ones the 256-row tiles: both on a ragged mix
+    lens = [1, 37, 256, 300, 129, 64]
+    slots = [5, 0, 3, 1, 6, 2]
+    if tokens == "many":
+        lens += [320, 700, 800, 900, 701]          # 4204 tokens in all
+        slots += [10, 7, 11, 8, 9]
     wl = W.scaled(base, batch=len(lens), seqlen=max(lens), min_seqlen=None)
     assert B.gta_uses_tuned_kernels(B.config_of(wl), B.GTA_MODE_PREFILL) == 1
     rng = W.make_rng(wl)
@@ -248,8 +252,7 @@ def test_tuned_prefill_ragged_small(shape, with_wo, tokens):
     cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
     x = W.draw_hidden(wl, rng, int(cu[-1]))
     wdev = U.upload_weights(w, wl.dtype)
-    slots = [5, 0, 3, 1, 6, 2]
-    cache = U.DeviceCache(wl, 7, 320, fill=-3.0)
+    cache = U.DeviceCache(wl, 12, 904, fill=-3.0)
     out = U.run_prefill(wl, wdev, x, cu, cache=cache, slots=slots)
     ref, Kref, Cref = orc.prefill(U.oracle_config(wl), U.oracle_weights(w), x, cu)
     U.assert_close(U.f64(out), ref, wl.dtype, f"tuned prefill {shape}")

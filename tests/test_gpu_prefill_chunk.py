@@ -63,18 +63,21 @@ def test_prefix_then_chunk_equals_one_pass(shape, with_wo):
 
 
 @pytest.mark.parametrize("shape", ["1b", "paper"])
-def test_chunk_of_more_than_1024_tokens(shape):
-    """A chunk call beyond the short-prefill limit (256-row projection tiles with per-token RoPE rows):
-    chunks of 1200 and 50 tokens behind 100 and 650 cached rows."""
-    lens, pre = [1300, 700], [100, 650]
-    wl = W.scaled(_base(shape), batch=2, seqlen=1300, min_seqlen=None)
+def test_chunk_beyond_the_short_prefill_limit(shape):
+    """A chunk call with more tokens than the short-prefill kernels take (1536 at the 1B shape, 4096 at the
+    paper's): 256-row projection tiles with per-token RoPE rows.  A long and a short chunk behind 100 and
+    650 cached rows."""
+    long_len = 1900 if shape == "1b" else 4500
+    lens, pre = [long_len, 700], [100, 650]
+    wl = W.scaled(_base(shape), batch=2, seqlen=long_len, min_seqlen=None)
     w, cu, x = _inputs(wl, lens)
     wdev = U.upload_weights(w, wl.dtype)
-    cache = U.DeviceCache(wl, 2, 1312, fill=-3.0)
+    cache = U.DeviceCache(wl, 2, long_len + 12, fill=-3.0)
     xp = np.concatenate([x[cu[b]:cu[b] + pre[b]] for b in range(2)])
     U.run_prefill(wl, wdev, xp, np.array([0, 100, 750], dtype=np.int32), cache=cache)
     xc = np.concatenate([x[cu[b] + pre[b]:cu[b + 1]] for b in range(2)])
-    out = U.run_prefill_chunk(wl, wdev, xc, np.array([0, 1200, 1250], dtype=np.int32), cache)
+    cuc = np.array([0, long_len - 100, long_len - 100 + 50], dtype=np.int32)
+    out = U.run_prefill_chunk(wl, wdev, xc, cuc, cache)
     ref, Kref, Cref = orc.prefill(U.oracle_config(wl), U.oracle_weights(w), x, cu)
     ref_rows = np.concatenate([ref[cu[b] + pre[b]:cu[b + 1]] for b in range(2)])
     U.assert_close(U.f64(out), ref_rows, wl.dtype, f"long chunk {shape}")
