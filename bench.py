@@ -39,6 +39,7 @@ PEAK_HBM_GBPS = 8000.0        # MI355X HBM3E
 RECORDED_TRAFFIC_BYTES = {
     ("decode_b8_32k_bf16", "decode_attn_kernel"): 537.78e6 + 4.22e6,
     ("decode_b64_8k_bf16", "decode_attn_kernel"): 1079.08e6 + 4.26e6,
+    ("decode_b512_2k_bf16", "decode_attn_kernel"): 2157.77e6 + 4.81e6,
     ("prefill_1b_bf16", "attn_prefill_kernel"): 93.68e6 + 67.11e6,
     ("varlen_prefill_bf16", "attn_prefill_kernel"): 17472.04e6 + 1989.15e6,
     ("gta1b_prefill_b32_t2048", "attn_prefill_kernel"): 167.66e6 + 104.13e6,
@@ -111,7 +112,8 @@ def bench_decode(wl, steps, warmup, want_cpu_baseline):
     ctx = wl.seqlen + (warmup + steps) // 2
     cache_bytes = cm.decode_cache_bytes(wl, [ctx] * wl.batch)
     res = {
-        "workload": wl.name, "us_per_step": sec * 1e6, "us_per_token": sec * 1e6 / wl.batch,
+        "workload": wl.name, "batch": wl.batch, "context": wl.seqlen,
+        "us_per_step": sec * 1e6, "us_per_token": sec * 1e6 / wl.batch,
         "tokens_per_s": wl.batch / sec, "cache_GBps": cache_bytes / sec / 1e9,
         "frac_hbm_peak_whole_step": cache_bytes / sec / 1e9 / PEAK_HBM_GBPS,
     }
@@ -376,7 +378,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--only", choices=["decode32k", "decode8k", "prefill", "chunk", "varlen", "paper"], default=None,
+    ap.add_argument("--only", choices=["decode32k", "decode8k", "decode512", "prefill", "chunk", "varlen", "paper"], default=None,
                     help="measure one workload only (profiling runs)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run calibration_copy_kernel once on 512 MiB (reads 512 MiB, writes 512 MiB): "
@@ -404,6 +406,10 @@ def main():
         pre = bench_prefill(W.by_name("prefill_1b_bf16"), args.steps, args.warmup, cpu)
     if args.only in (None, "decode8k"):
         dec8 = bench_decode(W.by_name("decode_b64_8k_bf16"), args.steps, args.warmup, False)
+    dec512 = None
+    if args.only in (None, "decode512"):   # a serving-size batch: 512 sequences with 2048 cached tokens each
+        dec512 = bench_decode(W.scaled(W.by_name("decode_b64_8k_bf16"), batch=512, seqlen=2048, name="decode_b512_2k_bf16"),
+                              args.steps, args.warmup, False)
     chk = None
     if args.only in (None, "chunk"):    # second half of every sequence of the prefill workload behind the first
         chk = bench_prefill_chunk(W.by_name("prefill_1b_bf16"), 2048, args.steps, args.warmup)
@@ -422,7 +428,7 @@ def main():
         pap["prefill"]["roofline"]["kernel"] = "attn_prefill_kernel (heads of 64, latent 128)"
         pap["decode"]["roofline"]["kernel"] = "decode_narrow_kernel"
         pap["attention_vs_gqa"] = bench_attention_comparator(args.steps)
-    main_res = dec or pre or dec8 or var or (pap["prefill"] if pap else None)
+    main_res = dec or pre or dec8 or dec512 or var or (pap["prefill"] if pap else None)
     if main_res is None:   # --only chunk: the chunked figure alone
         print(json.dumps({"chunked_prefill": chk, "short_prefill_1b": short}))
         return
@@ -431,11 +437,11 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
     }
-    if main_res is dec or main_res is dec8:
+    if main_res is dec or main_res is dec8 or main_res is dec512:
         line.update({"value": main_res["cache_GBps"], "unit": "GB/s", "ms_per_step": main_res["us_per_step"] / 1e3,
                      "us_per_token": main_res["us_per_token"],
-                     "config": {"workload": main_res["workload"], "batch": main_res and W.by_name(main_res["workload"]).batch,
-                                "context": W.by_name(main_res["workload"]).seqlen, "value_is": "cache bytes / whole gta_decode step"}})
+                     "config": {"workload": main_res["workload"], "batch": main_res["batch"],
+                                "context": main_res["context"], "value_is": "cache bytes / whole gta_decode step"}})
     else:
         line.update({"value": main_res["tflops"], "unit": "TFLOP/s", "ms_per_step": main_res["ms_per_step"],
                      "config": {"workload": main_res["workload"], "value_is": "algorithmic flops / whole gta_prefill call"}})
@@ -449,6 +455,8 @@ def main():
         line["prefill"] = pre
     if dec8 is not None and main_res is not dec8:
         line["decode_b64_8k"] = dec8
+    if dec512 is not None and main_res is not dec512:
+        line["decode_b512_2k"] = dec512
     if var is not None and main_res is not var:
         line["varlen_prefill"] = var
     if chk is not None:
