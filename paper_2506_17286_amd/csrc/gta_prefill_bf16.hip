@@ -537,6 +537,7 @@ __global__ __launch_bounds__(T::NT) void attn_prefill_kernel(AttnArgs a) {
 }
 
 typedef AttnTile<128, 256> AttnWide;     // d_h = 128, latent width a multiple of 256
+typedef AttnTile<128, 128> AttnMid;      // d_h = 128, other latent widths that are multiples of 128
 typedef AttnTile<64, 128> AttnNarrow;    // d_h = 64, latent width a multiple of 128
 typedef AttnTile<64, 64> AttnSlim;       // d_h = 64, other latent widths that are multiples of 64 (e.g. the
                                          // GQA-degenerate setting d_l = d_h used as a comparator)
@@ -558,7 +559,7 @@ bool attn_prefill_supported(const Dims &d, int max_len) {
   // byte offsets inside one sequence's K / C rows are kept in 32 bits
   if ((int64_t)max_len * d.wc_w * 2 >= ((int64_t)1 << 31) || (int64_t)max_len * d.wk_w * 2 >= ((int64_t)1 << 31)) return false;
   if (d.dtype != GTA_BF16 || d.wq_w % 8 || d.wk_w % 8 || d.wc_w % 8) return false;
-  return (d.dh == 128 && d.dl % 256 == 0) || (d.dh == 64 && d.dl % 64 == 0);
+  return (d.dh == 128 && d.dl % 128 == 0) || (d.dh == 64 && d.dl % 64 == 0);
 }
 
 static AttnArgs attn_args(const Dims &d, const void *q, const void *k, const void *c, const int32_t *cu, int batch,
@@ -576,7 +577,8 @@ void launch_attn_prefill_bf16(const Dims &d, const void *q, const void *k, const
                               int batch, int64_t total, int max_len, void *L, hipStream_t st) {
   AttnArgs a = attn_args(d, q, k, c, cu, batch, total);
   a.L = (bf16 *)L;
-  if (d.dh == 128) launch_attn<AttnWide, false>(a, d, batch, max_len, st);
+  if (d.dh == 128 && d.dl % 256 == 0) launch_attn<AttnWide, false>(a, d, batch, max_len, st);
+  else if (d.dh == 128) launch_attn<AttnMid, false>(a, d, batch, max_len, st);
   else if (d.dl % 128 == 0) launch_attn<AttnNarrow, false>(a, d, batch, max_len, st);
   else launch_attn<AttnSlim, false>(a, d, batch, max_len, st);
 }
@@ -608,8 +610,10 @@ void launch_attn_chunk_bf16(const Dims &d, const void *q, const gta_cache &cache
     a.wp = (const bf16 *)wp; a.gate = d.gate ? (const bf16 *)gate : nullptr; a.out = (bf16 *)out;
     a.hpq = d.hpq; a.dh = d.dh; a.nh = d.nh; a.gate_kind = d.gate;
     launch_attn<AttnNarrow, true>(a, d, batch, max_chunk, st);
-  } else if (d.dh == 128) {
+  } else if (d.dh == 128 && d.dl % 256 == 0) {
     launch_attn<AttnWide, false>(a, d, batch, max_chunk, st);
+  } else if (d.dh == 128) {
+    launch_attn<AttnMid, false>(a, d, batch, max_chunk, st);
   } else if (d.dl % 128 == 0) {
     launch_attn<AttnNarrow, false>(a, d, batch, max_chunk, st);
   } else {

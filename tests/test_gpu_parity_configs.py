@@ -213,7 +213,7 @@ def test_tuned_decode_large_batches(shape, batch, with_wo):
 @pytest.mark.parametrize("shape,with_wo", [("1b", False), ("1b", True), ("wide", False), ("paper", False),
                                            ("paper", True), ("packed128", False), ("slim", False),
                                            ("paper_nq3", True), ("paper_nq6", False), ("paper_nc2", False),
-                                           ("packed128_pad", False)])
+                                           ("packed128_pad", False), ("mid384", True)])
 @pytest.mark.parametrize("tokens", ["few", "many"])
 def test_tuned_prefill_ragged_small(shape, with_wo, tokens):
     """The MFMA prefill path (1B and wide shapes, the paper's own layer shape with heads of 64 and one
@@ -234,6 +234,8 @@ def test_tuned_prefill_ragged_small(shape, with_wo, tokens):
         base = W.scaled(W.WORKLOADS[1], d_model=512, n_heads=4, n_qgroups=2, n_kgroups=1, n_cgroups=1, latent_dim=128)
     elif shape == "packed128_pad":   # heads of 128, summed width 768 + 128 + 256 + 768 = 7.5 tiles of 256
         base = W.scaled(W.WORKLOADS[1], d_model=512, n_heads=6, n_qgroups=6, n_kgroups=1, n_cgroups=1, latent_dim=256)
+    elif shape == "mid384":   # heads of 128 with a latent of 384: the 128-column attention tile, three per group
+        base = W.scaled(W.WORKLOADS[1], d_model=512, n_heads=4, n_qgroups=2, n_kgroups=2, n_cgroups=1, latent_dim=384)
     elif shape == "slim":   # GQA-like: one map per head, latent as wide as a head, several key / latent groups
         base = W.scaled(W.PAPER_WORKLOADS[0], d_model=512, n_heads=8, n_qgroups=8, n_kgroups=2, n_cgroups=2, latent_dim=64)
     else:
