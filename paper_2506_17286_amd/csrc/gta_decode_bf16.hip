@@ -254,16 +254,26 @@ __global__ __launch_bounds__(256, S::OCC) void decode_attn_kernel(DecAttnArgs a,
   }
   __syncthreads();
 
-  // this lane's slice of every query it scores against
-  float qf[KCH][QPK][8];
+  // this lane's slice of every query it scores against, as bf16 pairs: scores and the map-times-latent
+  // update are bf16 dot products with fp32 sums (v_dot2_f32_bf16), the precision the prefill kernels
+  // give the same products; two rows per instruction in the update
+  typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+  static_assert(R % 2 == 0, "rows are taken in pairs");
+  bf16x2 qh[KCH][QPK][4];
 #pragma unroll
   for (int i = 0; i < KCH; ++i)
 #pragma unroll
     for (int u = 0; u < QPK; ++u) {
       const int g = (i * GPL + lane / LPG) * QPK + u;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) qf[i][u][e] = qs[g * DH + (lane % LPG) * 8 + e];
+      for (int w = 0; w < 4; ++w) {
+        bf16x2 t;
+        t[0] = (bf16)qs[g * DH + (lane % LPG) * 8 + 2 * w];
+        t[1] = (bf16)qs[g * DH + (lane % LPG) * 8 + 2 * w + 1];
+        qh[i][u][w] = t;
+      }
     }
+  const bf16x2 ones = {(bf16)1.0f, (bf16)1.0f};
   auto compute = [&](const u32x4 (&kb)[R][KCH], const u32x4 (&cb)[R][CCH], int nv) {
     float p[R][KCH][QPK];
     // scores of R keys against this lane's groups (log2 domain)
@@ -271,19 +281,20 @@ __global__ __launch_bounds__(256, S::OCC) void decode_attn_kernel(DecAttnArgs a,
     for (int r = 0; r < R; ++r)
 #pragma unroll
       for (int i = 0; i < KCH; ++i) {
-        float kf[8];
-        unpack8(kb[r][i], kf);
+        const unsigned kw[4] = {kb[r][i].x, kb[r][i].y, kb[r][i].z, kb[r][i].w};
 #pragma unroll
         for (int u = 0; u < QPK; ++u) {
           float a = 0.f;
 #pragma unroll
-          for (int e = 0; e < 8; ++e) a = fmaf(qf[i][u][e], kf[e], a);
+          for (int w = 0; w < 4; ++w) a = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, kw[w]), qh[i][u][w], a, false);
           a = group_sum<LPG>(a);
           p[r][i][u] = r < nv ? a : -INFINITY;
         }
       }
-    // online softmax over the block
+    // online softmax over the block; probabilities rounded to bf16 in row pairs, the row sum is the sum
+    // of the rounded values
     float corr[KCH][QPK];
+    int pk[R / 2][KCH][QPK];
     bool changed = false;
 #pragma unroll
     for (int i = 0; i < KCH; ++i)
@@ -293,12 +304,19 @@ __global__ __launch_bounds__(256, S::OCC) void decode_attn_kernel(DecAttnArgs a,
 #pragma unroll
         for (int r = 1; r < R; ++r) bm = fmaxf(bm, p[r][i][u]);
         const float mn = fmaxf(m[i][u], bm);
-        corr[i][u] = fast_exp2(m[i][u] - mn);
+        const float ref = mn > -INFINITY ? mn : 0.f;   // nothing seen yet and nothing valid here
+        corr[i][u] = fast_exp2(m[i][u] - ref);
         changed |= (mn != m[i][u]);
-        float ps = 0.f;
+        float ps = l[i][u] * corr[i][u];
 #pragma unroll
-        for (int r = 0; r < R; ++r) { p[r][i][u] = fast_exp2(p[r][i][u] - mn); ps += p[r][i][u]; }
-        l[i][u] = l[i][u] * corr[i][u] + ps;
+        for (int rp = 0; rp < R / 2; ++rp) {
+          bf16x2 t;
+          t[0] = (bf16)fast_exp2(p[2 * rp][i][u] - ref);
+          t[1] = (bf16)fast_exp2(p[2 * rp + 1][i][u] - ref);
+          pk[rp][i][u] = __builtin_bit_cast(int, t);
+          ps = __builtin_amdgcn_fdot2_f32_bf16(t, ones, ps, false);
+        }
+        l[i][u] = ps;
         m[i][u] = mn;
       }
     if (__any(changed)) {
@@ -312,19 +330,26 @@ __global__ __launch_bounds__(256, S::OCC) void decode_attn_kernel(DecAttnArgs a,
           for (int e = 0; e < 8; ++e) acc[j][v][e] *= cg;
         }
     }
-    // L_g += p_g * c  for every map group fed by this latent chunk
+    // L_g += p_g * c  for every map group fed by this latent chunk, two rows at a time: word e of cx is
+    // (row A's element e, row B's element e)
 #pragma unroll
-    for (int r = 0; r < R; ++r)
+    for (int rp = 0; rp < R / 2; ++rp)
 #pragma unroll
       for (int j = 0; j < CCH; ++j) {
-        float cf[8];
-        unpack8(cb[r][j], cf);
+        const unsigned ca[4] = {cb[2 * rp][j].x, cb[2 * rp][j].y, cb[2 * rp][j].z, cb[2 * rp][j].w};
+        const unsigned cbv[4] = {cb[2 * rp + 1][j].x, cb[2 * rp + 1][j].y, cb[2 * rp + 1][j].z, cb[2 * rp + 1][j].w};
+        bf16x2 cx[8];
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+          cx[2 * w] = __builtin_bit_cast(bf16x2, __builtin_amdgcn_perm(cbv[w], ca[w], 0x05040100u));
+          cx[2 * w + 1] = __builtin_bit_cast(bf16x2, __builtin_amdgcn_perm(cbv[w], ca[w], 0x07060302u));
+        }
 #pragma unroll
         for (int v = 0; v < QPC; ++v) {
           const int g = (j / DLC) * QPC + v, t = g / QPK;
-          const float pg = lane_bcast(p[r][t / GPL][g % QPK], (t % GPL) * LPG);
+          const bf16x2 pg = __builtin_bit_cast(bf16x2, __builtin_amdgcn_readlane(pk[rp][t / GPL][g % QPK], (t % GPL) * LPG));
 #pragma unroll
-          for (int e = 0; e < 8; ++e) acc[j][v][e] = fmaf(pg, cf[e], acc[j][v][e]);
+          for (int e = 0; e < 8; ++e) acc[j][v][e] = __builtin_amdgcn_fdot2_f32_bf16(cx[e], pg, acc[j][v][e], false);
         }
       }
   };
