@@ -98,7 +98,10 @@ __global__ __launch_bounds__(256, S::OCC) void decode_attn_kernel(DecAttnArgs a,
   constexpr int KROW = S::NK * DH / 8, CROW = S::NC * DL / 8;   // 16-byte words per cache row
   constexpr int WQ = NQ * DH, WK = S::NK * DH, WC = S::NC * DL;
   __shared__ float sm[kWaves][NQ], sl[kWaves][NQ];
-  __shared__ float lacc[NQ * DL];
+  // merge area: one copy per wave where that fits beside a second workgroup (one barrier instead of
+  // four rounds), else one copy that the waves add to in turn
+  constexpr bool kOnePass = kWaves * NQ * DL * 4 <= 32 * 1024;
+  __shared__ float lacc[(kOnePass ? kWaves : 1) * NQ * DL];
   __shared__ float qs[WQ];                                       // rotated queries * scale * log2(e)
   __shared__ __attribute__((aligned(16))) bf16 newrow[WK + WC];  // fused step: the new token's k | c row
 
@@ -400,24 +403,43 @@ __global__ __launch_bounds__(256, S::OCC) void decode_attn_kernel(DecAttnArgs a,
       for (int w = 1; w < kWaves; ++w) mx = fmaxf(mx, sm[w][g]);
       wscale[j][v] = sm[wave][g] > -INFINITY ? fast_exp2(sm[wave][g] - mx) : 0.f;
     }
-  for (int w = 0; w < kWaves; ++w) {
-    if (wave == w) {
+  if constexpr (kOnePass) {
 #pragma unroll
-      for (int j = 0; j < CCH; ++j)
+    for (int j = 0; j < CCH; ++j)
 #pragma unroll
-        for (int v = 0; v < QPC; ++v) {
-          const int g = (j / DLC) * QPC + v;
-          float *dst = lacc + g * DL + (j % DLC) * 512 + lane * 8;
+      for (int v = 0; v < QPC; ++v) {
+        const int g = (j / DLC) * QPC + v;
+        float *dst = lacc + wave * NQ * DL + g * DL + (j % DLC) * 512 + lane * 8;
 #pragma unroll
-          for (int e = 0; e < 8; ++e) {
-            const float val = acc[j][v][e] * wscale[j][v];
-            dst[e] = (w == 0) ? val : dst[e] + val;
-          }
-        }
-    }
+        for (int e = 0; e < 8; ++e) dst[e] = acc[j][v][e] * wscale[j][v];
+      }
     __syncthreads();
+    for (int i = tid; i < NQ * DL; i += 256) {
+      float v = lacc[i];
+#pragma unroll
+      for (int w = 1; w < kWaves; ++w) v += lacc[w * NQ * DL + i];   // fixed order
+      pa[i] = v;
+    }
+  } else {
+    for (int w = 0; w < kWaves; ++w) {
+      if (wave == w) {
+#pragma unroll
+        for (int j = 0; j < CCH; ++j)
+#pragma unroll
+          for (int v = 0; v < QPC; ++v) {
+            const int g = (j / DLC) * QPC + v;
+            float *dst = lacc + g * DL + (j % DLC) * 512 + lane * 8;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+              const float val = acc[j][v][e] * wscale[j][v];
+              dst[e] = (w == 0) ? val : dst[e] + val;
+            }
+          }
+      }
+      __syncthreads();
+    }
+    for (int i = tid; i < NQ * DL; i += 256) pa[i] = lacc[i];
   }
-  for (int i = tid; i < NQ * DL; i += 256) pa[i] = lacc[i];
   if (tid < NQ) {
     const int g = tid;
     float mx = sm[0][g];
