@@ -474,7 +474,7 @@ __global__ __launch_bounds__(256) void decode_narrow_kernel(DecAttnArgs a, RopeF
   static_assert((NC == 1 || NC == 2) && NQ % NC == 0, "one or two latents");
   static_assert(WQ / 2 <= 512 && WC <= 256, "prologue mapping");
   __shared__ float sm[kWaves][NQ], sl[kWaves][NQ];
-  __shared__ float lacc[NQ * DL];
+  __shared__ float lacc[kWaves * NQ * DL];   // one copy per wave: they merge in one pass
   __shared__ float qs[WQ];                                       // rotated queries * scale * log2(e)
   __shared__ __attribute__((aligned(16))) bf16 newrow[WK + WC];  // fused step: the new token's k | c row
 
@@ -743,27 +743,27 @@ __global__ __launch_bounds__(256) void decode_narrow_kernel(DecAttnArgs a, RopeF
     for (int g = 0; g < NQ; ++g) { sm[wave][g] = mw[g]; sl[wave][g] = lw[g]; }
   }
   __syncthreads();
-  for (int w = 0; w < kWaves; ++w) {
-    if (wave == w && lane < CROW) {   // lanes of stream 0 hold the wave's sums: latent cgl, elements (lane % 16) * 8 ..
+  if (lane < CROW) {   // lanes of stream 0 hold the wave's sums: latent cgl, elements (lane % 16) * 8 ..
 #pragma unroll
-      for (int v = 0; v < QPC; ++v) {
-        const int g = cgl * QPC + v;
-        float mx = sm[0][g];
+    for (int v = 0; v < QPC; ++v) {
+      const int g = cgl * QPC + v;
+      float mx = sm[0][g];
 #pragma unroll
-        for (int x = 1; x < kWaves; ++x) mx = fmaxf(mx, sm[x][g]);
-        const float mine = sm[w][g];
-        const float ws = mine > -INFINITY ? fast_exp2(mine - mx) : 0.f;
-        float *dst = lacc + g * DL + (lane & 15) * 8;
+      for (int x = 1; x < kWaves; ++x) mx = fmaxf(mx, sm[x][g]);
+      const float mine = sm[wave][g];
+      const float ws = mine > -INFINITY ? fast_exp2(mine - mx) : 0.f;
+      float *dst = lacc + wave * NQ * DL + g * DL + (lane & 15) * 8;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          const float val = acc[v][e] * ws;
-          dst[e] = (w == 0) ? val : dst[e] + val;
-        }
-      }
+      for (int e = 0; e < 8; ++e) dst[e] = acc[v][e] * ws;
     }
-    __syncthreads();
   }
-  for (int i = tid; i < NQ * DL; i += 256) pa[i] = lacc[i];
+  __syncthreads();
+  for (int i = tid; i < NQ * DL; i += 256) {
+    float v = lacc[i];
+#pragma unroll
+    for (int w = 1; w < kWaves; ++w) v += lacc[w * NQ * DL + i];   // fixed order
+    pa[i] = v;
+  }
   if (tid < NQ) {
     const int g = tid;
     float mx = sm[0][g];
