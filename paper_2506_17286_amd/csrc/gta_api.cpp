@@ -80,7 +80,7 @@ PrefillWs carve_prefill(const Dims &d, bool tuned, bool with_wo, int batch, int6
 
 int choose_splits(const Dims &d, int batch, int max_seq, int requested) {
   if (requested > 0) return requested > 1024 ? 1024 : requested;
-  // enough (sequence, split) blocks to put ~2 on every one of the 256 CUs (one where only one fits), but
+  // enough (sequence, split) blocks to put one or two on every one of the 256 CUs (the kernel's choice), but
   // no split shorter than 256 cached rows.
   const int target = tuned_decode_target_workgroups(d);
   int want = (target + batch - 1) / batch;

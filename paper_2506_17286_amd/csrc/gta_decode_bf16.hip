@@ -1376,15 +1376,16 @@ bool tuned_decode_supported(const Dims &d) {
   return matches<Shape1B>(d) || matches<ShapeWide>(d) || narrow_shape(d);
 }
 
-// Workgroups the split-K launch should have: two per CU, or one where the kernel's registers let only
-// one workgroup live on a CU and 512 would run in two rounds (the two-latent narrow kernel: batch 64,
-// 82 us per step with 8 splits against 65 us with 4; the 8 x 128 + 1024 kernel: batch 8 at 16K rows,
-// 163 us with 64 splits against 137 us with 32).
+// Workgroups the split-K launch should have.  One per CU for the wide-row kernels and the two-latent
+// narrow kernel: measured at the 1B shape with slot strides as the benchmark has them, 256 against 512
+// workgroups: batch 8 at 32K rows 102 against 105 us per step, batch 16 at 8K 64 against 66, batch 32
+// at 8K 110 against 111, batch 64 at 8K 197 against 199 (fewer partials to write and merge, longer
+// slices per workgroup); the 8 x 128 + 1024 kernel and the two-latent narrow kernel keep only one
+// workgroup per CU resident, so 512 would run in two rounds (163 -> 137 us, 82 -> 65 us).  The
+// one-latent narrow kernel (384-byte rows, 50 MB per step) prefers two per CU: 41 against 44 us.
 int tuned_decode_target_workgroups(const Dims &d) {
   if (d.dtype != GTA_BF16) return 512;
-  if (matches<ShapeWide>(d) && ShapeWide::OCC == 1) return 256;
-  if (narrow_shape(d) && d.nc == 2) return 256;
-  return 512;
+  return narrow_shape(d) && d.nc == 1 ? 512 : 256;
 }
 
 // The one-sequence tail kernel holds up to 64 splits; beyond that the general tail takes over, which
