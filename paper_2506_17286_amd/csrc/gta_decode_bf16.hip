@@ -1312,6 +1312,8 @@ void launch_tail(const Dims &d, const float *pacc, const float *pml, const Decod
   dim3 grid(d.nh, (batch + ROWS - 1) / ROWS);
   const size_t red = (size_t)(8 * ROWS * d.dh > 2048 ? 8 * ROWS * d.dh : 2048);
   const size_t smem = ((size_t)ROWS * d.dl + red + (size_t)ROWS * ws.splits) * sizeof(float);
+  // eight rows of a 1024-wide latent pass the 64 KiB a kernel gets without asking
+  if (smem > 64 * 1024) allow_dynamic_lds((const void *)decode_tail_kernel<TO, ROWS>, 160 * 1024);
   decode_tail_kernel<TO, ROWS><<<grid, 512, smem, st>>>(d, pacc, pml, ws.oldlen, ws.splits, batch, gs.g, gs.nsum,
                                                         gs.kstride, gs.ld, wp, out, cache.seq_lens, cache.status,
                                                         slots, cache.max_batch);
