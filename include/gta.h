@@ -14,15 +14,19 @@
  *   - Pointers marked "device" are HIP device memory owned by the caller, 16-byte aligned,
  *     dense row-major.  Config/weight/cache structs are host memory, read only during the call.
  *   - The library allocates, frees and retains nothing.  Scratch memory comes in through
- *     `workspace` (device), sized by gta_workspace_bytes().
+ *     `workspace` (device), sized by gta_workspace_bytes(); gta_decode_static uses a fixed array
+ *     inside the library instead.
  *   - All work is enqueued on `hip_stream` (a hipStream_t passed as void*; NULL = the null
  *     stream).  No call synchronises with the host.
  *   - Return value: GTA_OK or a negative gta_status.  On a host-detected error nothing has been
  *     enqueued or written.  A sequence whose new rows would not fit its cache slot is detected on
  *     the device: nothing is stored for it, its output rows are zero-filled and
  *     cache->status[slot] is set to GTA_ERR_CACHE_FULL.
- *   - Re-entrant; no global state.  Two calls that touch the same cache slot, output or
- *     workspace must be ordered by the caller (same stream or events).
+ *   - Re-entrant.  Two calls that touch the same cache slot, output or workspace must be ordered
+ *     by the caller (same stream or events).  The only process state is a table of "this kernel may
+ *     use more than 64 KiB of LDS on this device" attributes, set idempotently on the first launch of
+ *     such a kernel per device (and the scratch address of gta_decode_static): make the first call of
+ *     each entry point and shape on a device OUTSIDE stream capture; later calls may be captured.
  */
 #ifndef GTA_H_
 #define GTA_H_
@@ -162,6 +166,24 @@ GTA_API int gta_prefill_chunk(const gta_config *cfg, const gta_weights *weights,
 GTA_API int gta_decode(const gta_config *cfg, const gta_weights *weights, const void *x_new,
                int32_t batch, const gta_cache *cache, const int32_t *slots, void *out,
                int32_t num_splits, void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* gta_decode for callers that cannot hand over a workspace they allocated: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, semantics and kernels
+ * as gta_decode, minus `workspace`: the scratch memory is a fixed array of GTA_STATIC_SCRATCH_BYTES that
+ * lives in the library's device image (one copy per GPU the library runs on, held until the process
+ * ends).  The call allocates and frees nothing.
+ *   - A call whose gta_workspace_bytes(cfg, GTA_MODE_DECODE, batch, 0, cache->max_seq, num_splits)
+ *     exceeds GTA_STATIC_SCRATCH_BYTES returns GTA_ERR_WORKSPACE and does nothing (32 MiB covers, e.g.,
+ *     64 sequences at the 1B layer shape with any context length; use gta_decode beyond that).
+ *   - All calls on one GPU share that GPU's array: calls that may overlap in time (different streams,
+ *     different host threads) race; order them.  The array keeps the last call's contents and nothing
+ *     in it needs clearing between calls.
+ *   - The first call on a device looks the array's address up (a runtime query, no allocation); make
+ *     it outside stream capture, like the first call of any entry point. */
+#define GTA_STATIC_SCRATCH_BYTES (32u << 20)
+GTA_API int gta_decode_static(const gta_config *cfg, const gta_weights *weights, const void *x_new,
+                      int32_t batch, const gta_cache *cache, const int32_t *slots, void *out,
+                      int32_t num_splits, void *hip_stream);
 
 /* Append already projected (and rotated) rows to the caches (App. B.1.3): pure data movement,
  * bit-exact.  Rows [cu_new[b], cu_new[b+1]) of k_new / c_new go to slot slots[b] at positions

@@ -22,7 +22,8 @@ GTA_OK = 0
 GTA_ERR_NULL, GTA_ERR_SHAPE, GTA_ERR_ALIGN, GTA_ERR_DTYPE = -1, -2, -3, -4
 GTA_ERR_UNSUPPORTED, GTA_ERR_WORKSPACE, GTA_ERR_HIP, GTA_ERR_CACHE_FULL = -5, -6, -7, -8
 
-EXPORTS = ["gta_workspace_bytes", "gta_prefill", "gta_prefill_chunk", "gta_decode", "gta_cache_append", "gta_strerror",
+GTA_STATIC_SCRATCH_BYTES = 32 << 20
+EXPORTS = ["gta_workspace_bytes", "gta_prefill", "gta_prefill_chunk", "gta_decode", "gta_decode_static", "gta_cache_append", "gta_strerror",
            "gta_uses_tuned_kernels", "gta_prefill_attention", "gta_decode_attention", "gta_decode_combine", "gta_calibration_copy",
            "gta_calibration_read", "gta_calibration_mfma"]
 
@@ -77,6 +78,8 @@ def load(path: Optional[str] = None) -> ctypes.CDLL:
     lib.gta_prefill_chunk.argtypes = [cfgp, wp, vp, vp, i32, i64, i32, cp, vp, vp, vp, sz, vp]
     lib.gta_decode.restype = ctypes.c_int
     lib.gta_decode.argtypes = [cfgp, wp, vp, i32, cp, vp, vp, i32, vp, sz, vp]
+    lib.gta_decode_static.restype = ctypes.c_int
+    lib.gta_decode_static.argtypes = [cfgp, wp, vp, i32, cp, vp, vp, i32, vp]
     lib.gta_cache_append.restype = ctypes.c_int
     lib.gta_cache_append.argtypes = [cfgp, cp, vp, vp, vp, vp, i32, i32, vp]
     lib.gta_prefill_attention.restype = ctypes.c_int
@@ -198,6 +201,16 @@ def gta_decode(cfg: gta_config, weights: gta_weights, x_new, batch: int, cache: 
                            _stream(stream))
     if check:
         _check(rc, "gta_decode")
+    return rc
+
+
+def gta_decode_static(cfg: gta_config, weights: gta_weights, x_new, batch: int, cache: gta_cache, slots, out,
+                      num_splits: int, stream=None, check: bool = True) -> int:
+    rc = load().gta_decode_static(ctypes.byref(cfg), ctypes.byref(weights), _ptr(x_new), batch,
+                                  ctypes.byref(cache) if cache is not None else None, _ptr(slots), _ptr(out),
+                                  num_splits, _stream(stream))
+    if check:
+        _check(rc, "gta_decode_static")
     return rc
 
 

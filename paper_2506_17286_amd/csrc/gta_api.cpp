@@ -1,5 +1,6 @@
 // C-ABI entry points of libgta: argument validation, workspace carve-up and dispatch to the
-// tuned bf16 kernels or the shape-generic kernels.  No device code in this file.
+// tuned bf16 kernels or the shape-generic kernels.  No kernels in this file; the only device object
+// is the fixed scratch array of gta_decode_static.
 #include <math.h>
 
 #include <algorithm>
@@ -132,6 +133,34 @@ static int check_cache(const gta_cache *c) {
 
 static const int kMaxBatch = 65535;  // grid.y / grid.z limit
 
+// ---- fixed scratch of gta_decode_static ---------------------------------------------------------
+// One copy per GPU the library runs on, held until the process ends.  `scratch` is only a host-side
+// stand-in for the symbol: host code never passes it to a kernel, it asks the runtime once per device
+// for that device's address of the array and uses the address from then on.
+static __device__ __align__(256) unsigned char scratch[GTA_STATIC_SCRATCH_BYTES];
+
+static const int kMaxDevices = 64;
+static void *scratch_of_device[kMaxDevices];   // device address of `scratch`, NULL until resolved
+static std::mutex scratch_mu;
+
+// Address of the current device's copy of the scratch array (resolved on the first call on a device).
+static int static_scratch(void **out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return GTA_ERR_HIP;
+  std::lock_guard<std::mutex> lock(scratch_mu);
+  if (!scratch_of_device[dev]) {
+    void *p = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) {
+      if (getenv("GTA_DEBUG")) fprintf(stderr, "libgta: hipGetSymbolAddress(scratch): %s\n", hipGetErrorString(e));
+      return GTA_ERR_HIP;
+    }
+    scratch_of_device[dev] = p;
+  }
+  *out = scratch_of_device[dev];
+  return GTA_OK;
+}
+
 static bool decode_is_tuned(const Dims &d, const gta_cache &c) {
   return tuned_decode_supported(d) && tuned_decode_layout_ok(c);
 }
@@ -263,6 +292,19 @@ int gta_decode(const gta_config *cfg, const gta_weights *weights, const void *x_
   hipStream_t st = (hipStream_t)hip_stream;
   if (decode_is_tuned(d, *cache)) return tuned_decode(d, *weights, x_new, batch, *cache, slots, out, ws, st);
   return generic_decode(d, *weights, x_new, batch, *cache, slots, out, ws, st);
+}
+
+int gta_decode_static(const gta_config *cfg, const gta_weights *weights, const void *x_new, int32_t batch,
+                      const gta_cache *cache, const int32_t *slots, void *out, int32_t num_splits, void *hip_stream) {
+  // the size check comes first: an oversized call is refused before anything else is touched
+  const size_t need = cache ? gta_workspace_bytes(cfg, GTA_MODE_DECODE, batch, 0, cache->max_seq, num_splits) : 0;
+  if (need > (size_t)GTA_STATIC_SCRATCH_BYTES) return GTA_ERR_WORKSPACE;
+  void *ws = nullptr;
+  const int rc = static_scratch(&ws);
+  if (rc != GTA_OK) return rc;
+  // nothing in the decode workspace has to start at zero: every word a kernel reads was written by an
+  // earlier kernel of the same call
+  return gta_decode(cfg, weights, x_new, batch, cache, slots, out, num_splits, ws, (size_t)GTA_STATIC_SCRATCH_BYTES, hip_stream);
 }
 
 int gta_prefill_attention(const gta_config *cfg, const void *q, const void *k, const void *c,
