@@ -20,8 +20,12 @@
  *     stream).  No call synchronises with the host.
  *   - Return value: GTA_OK or a negative gta_status.  On a host-detected error nothing has been
  *     enqueued or written.  A sequence whose new rows would not fit its cache slot is detected on
- *     the device: nothing is stored for it, its output rows are zero-filled and
- *     cache->status[slot] is set to GTA_ERR_CACHE_FULL.
+ *     the device and cache->status[slot] is set to GTA_ERR_CACHE_FULL.  gta_decode,
+ *     gta_prefill_chunk and gta_cache_append then leave the slot as it was (no row stored, length
+ *     unchanged) and the first two zero-fill the sequence's output rows.  (gta_prefill refuses
+ *     max_seqlen > cache->max_seq on the host; a slot whose block table lacks a page for some row
+ *     is flagged, its length is still set, rows without a page are not stored and the output rows
+ *     are computed as usual.)
  *   - Re-entrant.  Two calls that touch the same cache slot, output or workspace must be ordered
  *     by the caller (same stream or events).  The only process state is a table of "this kernel may
  *     use more than 64 KiB of LDS on this device" attributes, set idempotently on the first launch of
@@ -244,7 +248,13 @@ GTA_API int gta_calibration_mfma(int32_t workgroups, int32_t iters, void *sink, 
 GTA_API const char *gta_strerror(int code);
 
 /* 1 if the configuration runs on the tuned bf16 MFMA/streaming kernels, 0 if it runs on the
- * shape-generic kernels (still HIP, any dimensions), negative gta_status if invalid. */
+ * shape-generic kernels (still HIP, any dimensions, but 10-100x slower), negative gta_status if
+ * invalid.  Tuned: bf16, d_h 64 or 128, every projection width a multiple of 64 (of 128 for heads of
+ * 128), H a multiple of 128; decode in addition needs cache rows of a compiled shape: heads of 128
+ * with (n_k, n_q, n_c, d_l) in {(4,4,1,512), (8,8,1,1024), (4,8,1,512), (4,4,2,512), (4,8,2,512),
+ * (4,4,4,512)}, or one key of 64 with latents of 128: n_c = 1 with n_q in {3,5,6}, n_c = 2 with n_q in
+ * {6,10}.  With GTA_DEBUG set in the environment a bf16 call that takes the generic kernels says so
+ * on stderr. */
 GTA_API int gta_uses_tuned_kernels(const gta_config *cfg, int mode);
 
 #ifdef __cplusplus

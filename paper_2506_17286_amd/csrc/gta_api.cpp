@@ -165,6 +165,15 @@ static bool decode_is_tuned(const Dims &d, const gta_cache &c) {
   return tuned_decode_supported(d) && tuned_decode_layout_ok(c);
 }
 
+// With GTA_DEBUG set, a bf16 call that runs on the shape-generic kernels says so on stderr: those
+// kernels are one to two orders of magnitude slower than the tuned ones, and which shapes are tuned is
+// a closed list (gta_uses_tuned_kernels answers the same question without a call).
+static void note_generic_path(const Dims &d, const char *entry) {
+  if (d.dtype != GTA_BF16 || !getenv("GTA_DEBUG")) return;
+  fprintf(stderr, "libgta: %s runs on the shape-generic kernels (H=%d n_h=%d n_q=%d n_k=%d n_c=%d d_h=%d d_l=%d)\n",
+          entry, d.H, d.nh, d.nq, d.nk, d.nc, d.dh, d.dl);
+}
+
 }  // namespace gta
 
 using namespace gta;
@@ -244,6 +253,7 @@ int gta_prefill(const gta_config *cfg, const gta_weights *weights, const void *x
   hipStream_t st = (hipStream_t)hip_stream;
   if (tuned)
     return tuned_prefill(d, *weights, x, cu_seqlens, batch, total_tokens, max_seqlen, cache, slots, out, ws, st);
+  note_generic_path(d, "gta_prefill");
   return generic_prefill(d, *weights, x, cu_seqlens, batch, total_tokens, max_seqlen, cache, slots, out, ws, st);
 }
 
@@ -270,6 +280,7 @@ int gta_prefill_chunk(const gta_config *cfg, const gta_weights *weights, const v
   if (tuned)
     return tuned_prefill_chunk(d, *weights, x, cu_seqlens, batch, total_tokens, max_chunk, *cache, slots, out, ws,
                                (hipStream_t)hip_stream);
+  note_generic_path(d, "gta_prefill_chunk");
   return generic_prefill_chunk(d, *weights, x, cu_seqlens, batch, total_tokens, max_chunk, *cache, slots, out, ws,
                                (hipStream_t)hip_stream);
 }
@@ -291,6 +302,7 @@ int gta_decode(const gta_config *cfg, const gta_weights *weights, const void *x_
   if (ws.bytes > workspace_bytes) return GTA_ERR_WORKSPACE;
   hipStream_t st = (hipStream_t)hip_stream;
   if (decode_is_tuned(d, *cache)) return tuned_decode(d, *weights, x_new, batch, *cache, slots, out, ws, st);
+  note_generic_path(d, "gta_decode");
   return generic_decode(d, *weights, x_new, batch, *cache, slots, out, ws, st);
 }
 

@@ -1358,6 +1358,13 @@ void launch_attn(const Dims &d, DecAttnArgs a, const RopeFreq &rf, int batch, hi
 
 typedef DecShape<128, 4, 1, 1, 1, 8, 2> Shape1B;      // 4 maps, 4 keys of 128, one latent of 512
 typedef DecShape<128, 8, 1, 1, 2, 4, 1> ShapeWide;    // 8 maps, 8 keys of 128, one latent of 1024
+// other groupings of heads of 128 on the same kernel (a key row and every latent row are multiples of 1 KiB):
+typedef DecShape<128, 4, 2, 1, 1, 8, 2> ShapeQ8K4;    // 8 maps on 4 keys (two maps share a key), one latent of 512
+typedef DecShape<128, 4, 1, 2, 1, 4, 1> ShapeC2;      // 4 maps, 4 keys, two latents of 512 (two maps per latent)
+typedef DecShape<128, 4, 2, 2, 1, 4, 1> ShapeQ8K4C2;  // 8 maps on 4 keys and two latents of 512
+typedef DecShape<128, 4, 1, 4, 1, 2, 1> ShapeC4;      // 4 maps, each with its own key and its own latent of 512
+// X(shape) for every wide-row instantiation, in dispatch order
+#define GTA_WIDE_DECODE_SHAPES(X) X(Shape1B) X(ShapeWide) X(ShapeQ8K4) X(ShapeC2) X(ShapeQ8K4C2) X(ShapeC4)
 
 template <class S>
 bool matches(const Dims &d) {
@@ -1375,7 +1382,10 @@ static bool narrow_shape(const Dims &d) {
 
 bool tuned_decode_supported(const Dims &d) {
   if (d.dtype != GTA_BF16) return false;
-  return matches<Shape1B>(d) || matches<ShapeWide>(d) || narrow_shape(d);
+#define GTA_X(S) if (matches<S>(d)) return true;
+  GTA_WIDE_DECODE_SHAPES(GTA_X)
+#undef GTA_X
+  return narrow_shape(d);
 }
 
 // Workgroups the split-K launch should have.  One per CU for the wide-row kernels and the two-latent
@@ -1420,9 +1430,10 @@ static DecAttnArgs attn_args(const Dims &d, const gta_cache &cache, const int32_
 }
 
 static void launch_attn_any(const Dims &d, const DecAttnArgs &a, const RopeFreq &rf, int batch, hipStream_t st) {
-  if (matches<Shape1B>(d)) launch_attn<Shape1B>(d, a, rf, batch, st);
-  else if (matches<ShapeWide>(d)) launch_attn<ShapeWide>(d, a, rf, batch, st);
-  else if (d.nc == 2 && d.nq == 10) decode_narrow_kernel<10, 2><<<dim3(a.splits, batch), 256, 0, st>>>(a, rf);
+#define GTA_X(S) if (matches<S>(d)) { launch_attn<S>(d, a, rf, batch, st); return; }
+  GTA_WIDE_DECODE_SHAPES(GTA_X)
+#undef GTA_X
+  if (d.nc == 2 && d.nq == 10) decode_narrow_kernel<10, 2><<<dim3(a.splits, batch), 256, 0, st>>>(a, rf);
   else if (d.nc == 2) decode_narrow_kernel<6, 2><<<dim3(a.splits, batch), 256, 0, st>>>(a, rf);
   else if (d.nq == 3) decode_narrow_kernel<3><<<dim3(a.splits, batch), 256, 0, st>>>(a, rf);
   else if (d.nq == 5) decode_narrow_kernel<5><<<dim3(a.splits, batch), 256, 0, st>>>(a, rf);

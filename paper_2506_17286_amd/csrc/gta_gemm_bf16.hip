@@ -9,10 +9,14 @@
 // the MFMA row operand comes from the weight tile through the LDS transpose read of gfx950
 // (ds_read_b64_tr_b16: each lane receives 4 consecutive k of one n), the MFMA column operand is
 // a plain 16-byte LDS read of an X row.  Each lane then owns 4 consecutive output columns of one
-// output row, which makes the RoPE pairing (j, j + d_h/2) lane-local and the stores 8 bytes wide.
+// output row, which makes the RoPE pairing (j, j + d_h/2) lane-local.
 //
-// Workgroup tile BM x BN x BK with WGM x WGN waves of 32x32x16 MFMA tiles, global -> register ->
-// LDS staging with two LDS stages (one barrier per k-tile).
+// Workgroup tile BM x BN x BK with WGM x WGN waves of 32x32x16 MFMA tiles.  The 256 x 256 x 64 tiles
+// (one wave of 128 x 128 per SIMD) run the hand-pipelined main loop below: two LDS stages, global
+// loads two tiles ahead of the LDS writes in two register sets, one barrier per k-tile; their result
+// is rounded to bf16, parked in LDS in output layout and written with 16-byte row-contiguous stores.
+// The small tiles (64-row tiles of short prefills and of the decode step) take the plain two-stage
+// loop and store straight from the accumulator layout.
 #include <math.h>
 
 #include <type_traits>

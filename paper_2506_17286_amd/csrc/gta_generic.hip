@@ -555,8 +555,9 @@ __global__ void append_copy_kernel(CacheView cv, const char *k_new, const char *
   if (slot < 0 || slot >= cv.max_batch) return;
   const int p = cv.seq_lens[slot];
   if (p < 0 || (int64_t)p + n > cv.max_seq) return;
+  if (!rows_backed(cv.pm, slot, p, p + n)) return;   // a row of the range has no page: nothing is stored, the commit kernel flags the slot
   const int64_t src = (int64_t)cu_new[b] + j, dst = cache_row(cv.pm, cv.max_seq, slot, p + j);
-  if (dst < 0) return;   // no page: the commit kernel flags the slot
+  if (dst < 0) return;
   copy_row_any(k_new + src * krow_bytes, (char *)cv.k + dst * krow_bytes, krow_bytes);
   copy_row_any(c_new + src * crow_bytes, (char *)cv.c + dst * crow_bytes, crow_bytes);
 }

@@ -124,7 +124,16 @@ def test_paper_layer_decode_b64_t2048_bf16():
     _check_decode_workload(W.PAPER_WORKLOADS[1], check_seqs=list(range(64)))
 
 
-@pytest.mark.parametrize("shape", ["1b", "wide", "paper", "paper_nq3", "paper_nq6", "paper_nc2", "paper_nc2_nq6"])
+WIDE_ROW_GROUPINGS = {   # other head groupings the wide-row decode kernel is compiled for (heads of 128, d_l 512)
+    "q8k4": dict(n_heads=16, n_qgroups=8, n_kgroups=4, n_cgroups=1),      # two maps share a key
+    "c2": dict(n_heads=16, n_qgroups=4, n_kgroups=4, n_cgroups=2),        # two latents
+    "q8k4c2": dict(n_heads=16, n_qgroups=8, n_kgroups=4, n_cgroups=2),
+    "c4": dict(n_heads=8, n_qgroups=4, n_kgroups=4, n_cgroups=4),         # every map its own latent
+}
+
+
+@pytest.mark.parametrize("shape", ["1b", "wide", "paper", "paper_nq3", "paper_nq6", "paper_nc2", "paper_nc2_nq6",
+                                   "q8k4", "c2", "q8k4c2", "c4"])
 def test_tuned_decode_ragged_contexts(shape):
     """The streaming decode kernels (wide rows, and the narrow-row kernel of the paper's own layer
     shapes) on ragged context lengths incl. 0, 1, block tails and empty splits, every output element
@@ -139,6 +148,8 @@ def test_tuned_decode_ragged_contexts(shape):
         base = W.scaled(W.PAPER_WORKLOADS[1], n_qgroups=10, n_cgroups=2)
     elif shape == "paper_nc2_nq6":
         base = W.scaled(W.PAPER_WORKLOADS[1], d_model=768, n_heads=12, n_qgroups=6, n_cgroups=2)
+    elif shape in WIDE_ROW_GROUPINGS:
+        base = W.scaled(W.WORKLOADS[2], **WIDE_ROW_GROUPINGS[shape])
     else:
         base = W.WORKLOADS[2] if shape == "1b" else W.scaled(W.WORKLOADS[4], kind="decode", min_seqlen=None)
     ctx = [0, 1, 7, 8, 31, 32, 33, 255, 777, 1500]
@@ -228,7 +239,8 @@ def test_tuned_decode_large_batches(shape, batch, with_wo):
 @pytest.mark.parametrize("shape,with_wo", [("1b", False), ("1b", True), ("wide", False), ("paper", False),
                                            ("paper", True), ("packed128", False), ("slim", False),
                                            ("paper_nq3", True), ("paper_nq6", False), ("paper_nc2", False),
-                                           ("packed128_pad", False), ("mid384", True)])
+                                           ("packed128_pad", False), ("mid384", True), ("q8k4c2", False),
+                                           ("c4", True)])
 @pytest.mark.parametrize("tokens", ["few", "many"])
 def test_tuned_prefill_ragged_small(shape, with_wo, tokens):
     """The MFMA prefill path (1B and wide shapes, the paper's own layer shape with heads of 64 and one
@@ -253,6 +265,8 @@ def test_tuned_prefill_ragged_small(shape, with_wo, tokens):
         base = W.scaled(W.WORKLOADS[1], d_model=512, n_heads=4, n_qgroups=2, n_kgroups=2, n_cgroups=1, latent_dim=384)
     elif shape == "slim":   # GQA-like: one map per head, latent as wide as a head, several key / latent groups
         base = W.scaled(W.PAPER_WORKLOADS[0], d_model=512, n_heads=8, n_qgroups=8, n_kgroups=2, n_cgroups=2, latent_dim=64)
+    elif shape in WIDE_ROW_GROUPINGS:   # several maps per key / several latents at heads of 128
+        base = W.scaled(W.WORKLOADS[1], **WIDE_ROW_GROUPINGS[shape])
     else:
         base = W.WORKLOADS[1] if shape == "1b" else W.WORKLOADS[4]
     # calls of few tokens take the short-prefill kernels (split-K projection on 64-row tiles; the limit

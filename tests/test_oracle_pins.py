@@ -90,6 +90,50 @@ def test_degenerate_setting_is_grouped_query_attention():
     np.testing.assert_allclose(got, ref, rtol=0, atol=1e-12)
 
 
+def test_gva_setting_shares_one_map_among_heads_with_their_own_values():
+    """Sec. 3.1, "Grouping Values to Share Attention Matrix": one attention map per group of heads,
+    every head its own value projection.  As a GTA setting: n_q = n_k = n_c = groups, the group's
+    latent holds its heads' values side by side (d_l = heads-per-group * d_h), W_{P,i} selects head
+    i's slice, gate off.  Checked against torch's attention with the group's q, k repeated per head."""
+    rng = np.random.default_rng(3)
+    n_h, G, dh, H, T = 6, 2, 4, 10, 19
+    hpq = n_h // G
+    cfg = orc.OracleConfig(H, n_h, G, G, G, dh, hpq * dh, gate=False)
+    w = _weights(rng, cfg)
+    w.wp = np.zeros((n_h, hpq * dh, dh))
+    for i in range(n_h):
+        w.wp[i, (i % hpq) * dh:(i % hpq + 1) * dh, :] = np.eye(dh)
+    x = rng.standard_normal((T, H))
+    got, _, C = orc.prefill_sequence(cfg, w, x)
+    q = np.repeat((x @ w.wq).reshape(T, G, dh).transpose(1, 0, 2), hpq, axis=0).copy()
+    k = np.repeat((x @ w.wk).reshape(T, G, dh).transpose(1, 0, 2), hpq, axis=0).copy()
+    v = (x @ w.wc).reshape(T, n_h, dh).transpose(1, 0, 2).copy()     # head i's own values: columns i*dh.. of X W_C
+    ref = _sdpa(q, k, v).transpose(1, 0, 2).reshape(T, n_h * dh)
+    np.testing.assert_allclose(got, ref, rtol=0, atol=1e-12)
+    assert C.shape == (T, n_h * dh)      # the cache holds a full set of values: what GVA does not save
+
+
+def test_gha_setting_shares_query_key_and_a_value_source_within_a_group():
+    """Sec. 3.1, "Grouping Heads to Compress Attention": the heads of a group share query and key and
+    derive their values from one shared source.  As a GTA setting: n_q = n_k = n_c = groups, the
+    latent is the shared source (d_l = d_h here), W_{P,i} a dense per-head map, gate off: GTA without
+    its nonlinearity.  Checked against torch's attention on V_i = C_g W_{P,i} built per head."""
+    rng = np.random.default_rng(4)
+    n_h, G, dh, H, T = 6, 3, 4, 10, 17
+    hpq = n_h // G
+    cfg = orc.OracleConfig(H, n_h, G, G, G, dh, dh, gate=False)
+    w = _weights(rng, cfg)
+    x = rng.standard_normal((T, H))
+    got, _, C = orc.prefill_sequence(cfg, w, x)
+    q = np.repeat((x @ w.wq).reshape(T, G, dh).transpose(1, 0, 2), hpq, axis=0).copy()
+    k = np.repeat((x @ w.wk).reshape(T, G, dh).transpose(1, 0, 2), hpq, axis=0).copy()
+    src = (x @ w.wc).reshape(T, G, dh)
+    v = np.stack([src[:, i // hpq, :] @ w.wp[i] for i in range(n_h)]).copy()
+    ref = _sdpa(q, k, v).transpose(1, 0, 2).reshape(T, n_h * dh)
+    np.testing.assert_allclose(got, ref, rtol=0, atol=1e-12)
+    assert C.shape == (T, G * dh)        # one shared source per group is all that is cached
+
+
 def test_rope_matches_complex_rotation_and_properties():
     rng = np.random.default_rng(3)
     T, n, d, base = 9, 2, 8, 10000.0
