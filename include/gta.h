@@ -203,6 +203,30 @@ GTA_API int gta_cache_append(const gta_config *cfg, const gta_cache *cache, cons
 /* ---- stage entry points: one stage of the pass on already projected inputs, in the launch
  * configuration gta_prefill / gta_decode use (for stage-wise tests and per-kernel timing). ---- */
 
+/* Projection stage of the prefill (Sec. 3.2 input projections and gate matrix; App. B.1.1 RoPE on q and
+ * k at positions counted from 0 within each sequence): [q | k | c | g] = x . [W_Q | W_K | W_C | W_G].
+ *   x, cu_seqlens, batch, total_tokens, max_seqlen  as for gta_prefill
+ *   q_out [total, n_q*d_h], k_out [total, n_k*d_h] (both rotated), c_out [total, n_c*d_l],
+ *   g_out [total, n_h*d_h] gate pre-activations; device, element type = cfg->dtype
+ *   workspace  mode PREFILL.  No cache is written.
+ * Tuned (bf16 MFMA) path only: GTA_ERR_UNSUPPORTED where gta_uses_tuned_kernels(cfg, PREFILL) is 0. */
+GTA_API int gta_prefill_projection(const gta_config *cfg, const gta_weights *weights, const void *x,
+                                   const int32_t *cu_seqlens, int32_t batch, int64_t total_tokens,
+                                   int32_t max_seqlen, void *q_out, void *k_out, void *c_out, void *g_out,
+                                   void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Value-decoder stage (Sec. 3.2 decoder equation applied after the map, as in the reformulated form
+ * of Sec. 3.3): out[t, i*d_h : (i+1)*d_h] = (l[t, q(i)*d_l : (q(i)+1)*d_l] . W_{P,i}) * gate(g[t, i*d_h : ..]).
+ *   l [total, n_q*d_l] normalised group outputs, g [total, n_h*d_h] gate pre-activations,
+ *   out [total, n_h*d_h]; device, element type = cfg->dtype.  Tuned path only (as above). */
+GTA_API int gta_prefill_decoder(const gta_config *cfg, const gta_weights *weights, const void *l, const void *g,
+                                int64_t total_tokens, void *out, void *hip_stream);
+
+/* Output projection (Sec. 3.3): out [total, H] = heads [total, n_h*d_h] . W_O; weights->wo required.
+ * Tuned path only (as above). */
+GTA_API int gta_output_projection(const gta_config *cfg, const gta_weights *weights, const void *heads,
+                                  int64_t total_tokens, void *out, void *hip_stream);
+
 /* Attention stage of the prefill (Sec. 3.3, reformulated form): for every map group g and token t,
  * l_out[t, g*d_l : (g+1)*d_l] = sum_{j<=t} Softmax_j(q_g[t].k_{k(g)}[j] / sqrt(d_h)) c_{c(g)}[j].
  *   q [total, n_q*d_h], k [total, n_k*d_h] (both already rotated), c [total, n_c*d_l],

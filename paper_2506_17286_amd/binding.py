@@ -24,7 +24,7 @@ GTA_ERR_UNSUPPORTED, GTA_ERR_WORKSPACE, GTA_ERR_HIP, GTA_ERR_CACHE_FULL = -5, -6
 
 GTA_STATIC_SCRATCH_BYTES = 32 << 20
 EXPORTS = ["gta_workspace_bytes", "gta_prefill", "gta_prefill_chunk", "gta_decode", "gta_decode_static", "gta_cache_append", "gta_strerror",
-           "gta_uses_tuned_kernels", "gta_prefill_attention", "gta_decode_attention", "gta_decode_combine", "gta_calibration_copy",
+           "gta_uses_tuned_kernels", "gta_prefill_projection", "gta_prefill_decoder", "gta_output_projection", "gta_prefill_attention", "gta_decode_attention", "gta_decode_combine", "gta_calibration_copy",
            "gta_calibration_read", "gta_calibration_mfma"]
 
 
@@ -82,6 +82,12 @@ def load(path: Optional[str] = None) -> ctypes.CDLL:
     lib.gta_decode_static.argtypes = [cfgp, wp, vp, i32, cp, vp, vp, i32, vp]
     lib.gta_cache_append.restype = ctypes.c_int
     lib.gta_cache_append.argtypes = [cfgp, cp, vp, vp, vp, vp, i32, i32, vp]
+    lib.gta_prefill_projection.restype = ctypes.c_int
+    lib.gta_prefill_projection.argtypes = [cfgp, wp, vp, vp, i32, i64, i32, vp, vp, vp, vp, vp, sz, vp]
+    lib.gta_prefill_decoder.restype = ctypes.c_int
+    lib.gta_prefill_decoder.argtypes = [cfgp, wp, vp, vp, i64, vp, vp]
+    lib.gta_output_projection.restype = ctypes.c_int
+    lib.gta_output_projection.argtypes = [cfgp, wp, vp, i64, vp, vp]
     lib.gta_prefill_attention.restype = ctypes.c_int
     lib.gta_prefill_attention.argtypes = [cfgp, vp, vp, vp, vp, i32, i64, i32, vp, vp]
     lib.gta_decode_attention.restype = ctypes.c_int
@@ -221,6 +227,35 @@ def gta_cache_append(cfg: gta_config, cache: gta_cache, slots, k_new, c_new, cu_
                                  _stream(stream))
     if check:
         _check(rc, "gta_cache_append")
+    return rc
+
+
+def gta_prefill_projection(cfg: gta_config, weights: gta_weights, x, cu_seqlens, batch: int, total_tokens: int,
+                           max_seqlen: int, q_out, k_out, c_out, g_out, workspace, stream=None, check: bool = True) -> int:
+    rc = load().gta_prefill_projection(ctypes.byref(cfg), ctypes.byref(weights), _ptr(x), _ptr(cu_seqlens), batch,
+                                       total_tokens, max_seqlen, _ptr(q_out), _ptr(k_out), _ptr(c_out), _ptr(g_out),
+                                       _ptr(workspace), 0 if workspace is None else workspace.numel() * workspace.element_size(),
+                                       _stream(stream))
+    if check:
+        _check(rc, "gta_prefill_projection")
+    return rc
+
+
+def gta_prefill_decoder(cfg: gta_config, weights: gta_weights, l, g, total_tokens: int, out, stream=None,
+                        check: bool = True) -> int:
+    rc = load().gta_prefill_decoder(ctypes.byref(cfg), ctypes.byref(weights), _ptr(l), _ptr(g), total_tokens, _ptr(out),
+                                    _stream(stream))
+    if check:
+        _check(rc, "gta_prefill_decoder")
+    return rc
+
+
+def gta_output_projection(cfg: gta_config, weights: gta_weights, heads, total_tokens: int, out, stream=None,
+                          check: bool = True) -> int:
+    rc = load().gta_output_projection(ctypes.byref(cfg), ctypes.byref(weights), _ptr(heads), total_tokens, _ptr(out),
+                                      _stream(stream))
+    if check:
+        _check(rc, "gta_output_projection")
     return rc
 
 

@@ -340,6 +340,62 @@ int gta_prefill_attention(const gta_config *cfg, const void *q, const void *k, c
   return check_launch();
 }
 
+int gta_prefill_projection(const gta_config *cfg, const gta_weights *weights, const void *x, const int32_t *cu_seqlens,
+                           int32_t batch, int64_t total_tokens, int32_t max_seqlen, void *q_out, void *k_out,
+                           void *c_out, void *g_out, void *workspace, size_t workspace_bytes, void *hip_stream) {
+  Dims d;
+  int rc = make_dims(cfg, &d);
+  if (rc != GTA_OK) return rc;
+  if ((rc = check_weights(weights)) != GTA_OK) return rc;
+  if (!x || !q_out || !k_out || !c_out || !g_out) return GTA_ERR_NULL;
+  if (batch <= 0 || batch > kMaxBatch || total_tokens < 0 || total_tokens > INT32_MAX || max_seqlen < 0)
+    return GTA_ERR_SHAPE;
+  if (!cu_seqlens && (total_tokens % batch != 0 || total_tokens / batch > max_seqlen)) return GTA_ERR_SHAPE;
+  if (misaligned(x) || misaligned(q_out) || misaligned(k_out) || misaligned(c_out) || misaligned(g_out) ||
+      ((uintptr_t)cu_seqlens & 3u))
+    return GTA_ERR_ALIGN;
+  if (!tuned_prefill_supported(d)) return GTA_ERR_UNSUPPORTED;
+  if (total_tokens == 0 || max_seqlen == 0) return GTA_OK;
+  if (!workspace || misaligned(workspace)) return GTA_ERR_WORKSPACE;
+  PrefillWs ws = carve_prefill(d, true, weights->wo != nullptr, batch, total_tokens, max_seqlen, workspace);
+  if (ws.bytes > workspace_bytes) return GTA_ERR_WORKSPACE;
+  ws.q = q_out; ws.k = k_out; ws.c = c_out; ws.g = g_out;
+  hipStream_t st = (hipStream_t)hip_stream;
+  launch_prefill_setup(d, cu_seqlens, batch, total_tokens, max_seqlen, ws.seq_id, ws.pos, ws.rope, nullptr, nullptr, st);
+  launch_proj_gemm(d, *weights, x, (int)total_tokens, ws, nullptr, nullptr, max_seqlen, st);
+  return check_launch();
+}
+
+int gta_prefill_decoder(const gta_config *cfg, const gta_weights *weights, const void *l, const void *g,
+                        int64_t total_tokens, void *out, void *hip_stream) {
+  Dims d;
+  int rc = make_dims(cfg, &d);
+  if (rc != GTA_OK) return rc;
+  if ((rc = check_weights(weights)) != GTA_OK) return rc;
+  if (!l || !g || !out) return GTA_ERR_NULL;
+  if (total_tokens < 0 || total_tokens > INT32_MAX) return GTA_ERR_SHAPE;
+  if (misaligned(l) || misaligned(g) || misaligned(out)) return GTA_ERR_ALIGN;
+  if (!tuned_prefill_supported(d)) return GTA_ERR_UNSUPPORTED;
+  if (total_tokens == 0) return GTA_OK;
+  launch_decoder_gemm(d, l, weights->wp, g, out, (int)total_tokens, (hipStream_t)hip_stream);
+  return check_launch();
+}
+
+int gta_output_projection(const gta_config *cfg, const gta_weights *weights, const void *heads, int64_t total_tokens,
+                          void *out, void *hip_stream) {
+  Dims d;
+  int rc = make_dims(cfg, &d);
+  if (rc != GTA_OK) return rc;
+  if ((rc = check_weights(weights)) != GTA_OK) return rc;
+  if (!weights->wo || !heads || !out) return GTA_ERR_NULL;
+  if (total_tokens < 0 || total_tokens > INT32_MAX) return GTA_ERR_SHAPE;
+  if (misaligned(heads) || misaligned(out)) return GTA_ERR_ALIGN;
+  if (!tuned_prefill_supported(d)) return GTA_ERR_UNSUPPORTED;
+  if (total_tokens == 0) return GTA_OK;
+  launch_plain_gemm(heads, d.wg_w, (int)total_tokens, d.H, d.wg_w, weights->wo, out, (hipStream_t)hip_stream);
+  return check_launch();
+}
+
 static int decode_stage_args(const gta_config *cfg, const gta_cache *cache, const int32_t *slots, int32_t batch,
                              int32_t num_splits, void *workspace, size_t workspace_bytes, Dims *d, DecodeWs *ws) {
   int rc = make_dims(cfg, d);

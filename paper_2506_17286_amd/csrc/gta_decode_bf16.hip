@@ -1496,7 +1496,12 @@ int tuned_decode(const Dims &d, const gta_weights &w, const void *x_new, int bat
     }
     return check_launch();
   }
-  if (w.wo) {
+  if (w.wo && gemm_shapes_supported(d)) {
+    // Sec. 3.3 output projection on the MFMA GEMM (64-row tiles), heads rounded to bf16 as in prefill
+    bf16 *Ob = reinterpret_cast<bf16 *>(ws.o);   // fp32-sized buffer, used as bf16
+    launch_tail_any<bf16>(d, pacc, pml, ws, batch, gs, (const bf16 *)w.wp, Ob, cache, slots, st);
+    launch_plain_gemm(Ob, d.wg_w, batch, d.H, d.wg_w, w.wo, out, st);
+  } else if (w.wo) {
     launch_tail_any<float>(d, pacc, pml, ws, batch, gs, (const bf16 *)w.wp, ws.o, cache, slots, st);
     generic_out_proj_f32in(d, w, ws.o, batch, out, st);
   } else {
