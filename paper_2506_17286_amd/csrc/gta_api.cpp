@@ -18,11 +18,16 @@ static int make_dims(const gta_config *c, Dims *out) {
   if (c->d_model <= 0 || c->n_heads <= 0 || c->n_qgroups <= 0 || c->n_kgroups <= 0 || c->n_cgroups <= 0 ||
       c->head_dim <= 0 || c->latent_dim <= 0)
     return GTA_ERR_SHAPE;
+  // every dimension is bounded before anything is multiplied or added (no overflow on hostile values)
+  const int32_t kMaxDim = 1 << 24;
+  if (c->d_model > kMaxDim || c->n_heads > kMaxDim || c->n_qgroups > kMaxDim || c->n_kgroups > kMaxDim ||
+      c->n_cgroups > kMaxDim || c->head_dim > kMaxDim || c->latent_dim > kMaxDim)
+    return GTA_ERR_UNSUPPORTED;
   if (c->n_heads % c->n_qgroups || c->n_qgroups % c->n_kgroups || c->n_qgroups % c->n_cgroups) return GTA_ERR_SHAPE;
   if (c->latent_dim < c->head_dim) return GTA_ERR_SHAPE;  // Sec. 3.2: d_l >= d_h
   if (c->rope && (c->head_dim % 2 || !(c->rope_base > 0.f))) return GTA_ERR_SHAPE;
   if (!(c->softmax_scale >= 0.f)) return GTA_ERR_SHAPE;
-  const int64_t wtot = (int64_t)(c->n_qgroups + c->n_kgroups + c->n_heads) * c->head_dim +
+  const int64_t wtot = ((int64_t)c->n_qgroups + c->n_kgroups + c->n_heads) * c->head_dim +
                        (int64_t)c->n_cgroups * c->latent_dim;
   if (wtot > (1 << 24) || c->d_model > (1 << 24) || (int64_t)c->n_qgroups * c->latent_dim > (1 << 24))
     return GTA_ERR_UNSUPPORTED;
