@@ -13,10 +13,12 @@
 //                                   column operand: P straight from the S^T accumulator registers)
 // so P never leaves registers and the per-query scale is a per-lane scalar.
 //
-// Online softmax runs in the log2 domain and is branch-free in the common case: the running
-// maximum of a query moves only when a block exceeds it by more than 2^8; the factor
-// exp2(m_old - m_new) always multiplies the row sum and reaches the 128 accumulator registers in a
-// rarely taken branch.  The lane pair of a query is reduced with v_permlane32_swap, P is packed
+// Online softmax runs in the log2 domain.  Around the diagonal the running maximum of a query moves
+// when a block exceeds it by more than 2^8, and the factor exp2(m_old - m_new) reaches the 128
+// accumulator registers in a rarely taken branch.  In the main loop (blocks entirely below the
+// diagonal) the block maximum is not formed at all: probabilities are taken relative to the maximum
+// the query already has, whatever their size, and only a row sum beyond 2^32 sends the wave through
+// the full step (bf16 probabilities and fp32 sums carry any scale; the final division cancels it).  The lane pair of a query is reduced with v_permlane32_swap, P is packed
 // with v_cvt_pk_bf16_f32 and summed with v_dot2_f32_bf16 (so the row sum is the sum of the rounded
 // values the MFMA sees).
 //
@@ -89,6 +91,7 @@ struct FusedDecoder {
 };
 
 constexpr float kLazyThreshold = 8.0f;   // log2 units
+constexpr float kRowSumLimit = 4294967296.0f;   // 2^32: a lane's sum of 16 probabilities that sends the wave to the full step
 
 // maximum / sum over the lane pair (l, l + 32) that shares a query
 __device__ __forceinline__ float pair_max(float v) {
@@ -359,32 +362,23 @@ __global__ __launch_bounds__(T::NT) void attn_prefill_kernel(AttnArgs a) {
     bf16x8 cf[NS + LA], pn[2];
 #pragma unroll
     for (int i = 0; i < LA; ++i) cf[i] = cread(i);
-    float b0, b1, b2, b3, b4, m_new = 0.f, negm = 0.f, ps = 0.f;
+    // Below the diagonal the running maximum is left where it is and the block's own maximum is not
+    // even formed: p = exp2(score - m_run) is taken as it comes and only its row sum is watched.  bf16
+    // probabilities and fp32 sums carry any scale, so nothing is lost while p stays far from the top
+    // of the fp32 range; a block whose row sum passes 2^32 (or is not finite) sends the whole wave
+    // through the full online-softmax step once, which moves the maximum and redoes the block.
+    float ps = 0.f;
+    const float negm = -m_run;
     const bf16x2 ones = {(bf16)1.0f, (bf16)1.0f};
-    auto soft_slice = [&](int k) {
-      if (k == 0) {
-        b0 = fmaxf(fmaxf(s[0], s[1]), s[2]); b1 = fmaxf(fmaxf(s[3], s[4]), s[5]); b2 = fmaxf(fmaxf(s[6], s[7]), s[8]);
-      } else if (k == 1) {
-        b3 = fmaxf(fmaxf(s[9], s[10]), s[11]); b4 = fmaxf(fmaxf(s[12], s[13]), s[14]); b0 = fmaxf(fmaxf(b0, b1), s[15]);
-      } else if (k == 2) {
-        b2 = fmaxf(fmaxf(b2, b3), b4);
-        b0 = pair_max(fmaxf(b0, b2));
-      } else if (k == 3) {
-        const float m_cand = b0 * a.scale_log2e;
-        m_new = m_cand > m_run + kLazyThreshold ? fmaxf(m_run, m_cand) : m_run;
-        corr = __builtin_amdgcn_exp2f(m_run - m_new);
-        m_run = m_new;
-        negm = -m_new;
-      } else if (k < 12) {
-        const int e = (k - 4) * 2;   // elements e, e+1 -> k-slots e%8, e%8+1 of pn[e/8]
+    auto soft_slice = [&](int k) {   // 16 slots; the 8 pairs of exponentials take the even ones
+      if (k % 2 == 0) {
+        const int e = k;   // elements e, e+1 -> k-slots e%8, e%8+1 of pn[e/8]
         const float p0 = __builtin_amdgcn_exp2f(fmaf(s[e], a.scale_log2e, negm));
         const float p1 = __builtin_amdgcn_exp2f(fmaf(s[e + 1], a.scale_log2e, negm));
         bf16x2 pk;
         pk[0] = (bf16)p0; pk[1] = (bf16)p1;
         pn[e >> 3][e & 7] = pk[0]; pn[e >> 3][(e & 7) + 1] = pk[1];
         ps = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, ps, false);
-      } else if (k == 12) {
-        l_run = fmaf(l_run, corr, ps);
       }
     };
 #pragma unroll
@@ -394,6 +388,12 @@ __global__ __launch_bounds__(T::NT) void attn_prefill_kernel(AttnArgs a) {
 #pragma unroll
       for (int k = i * SPS; k < (i + 1) * SPS; ++k) soft_slice(k);
       __builtin_amdgcn_sched_barrier(0);
+    }
+    if (__builtin_amdgcn_ballot_w64(!(ps < kRowSumLimit)) != 0) {   // rare
+      softmax(s, pn, corr);
+    } else {
+      l_run += ps;
+      corr = 1.f;
     }
     pf[0] = pn[0]; pf[1] = pn[1];
     __syncthreads();

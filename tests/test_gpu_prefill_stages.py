@@ -76,3 +76,48 @@ def test_stage_entry_points_refuse_the_generic_path():
     assert B.gta_prefill_projection(cfg, gw, t, None, 1, 128, 128, t, t, t, t, ws, check=False) == B.GTA_ERR_UNSUPPORTED
     assert B.gta_prefill_decoder(cfg, gw, t, t, 128, t, check=False) == B.GTA_ERR_UNSUPPORTED
     assert B.gta_output_projection(cfg, gw, t, 128, t, check=False) == B.GTA_ERR_UNSUPPORTED
+
+
+@pytest.mark.parametrize("shape", ["1b", "paper"])
+@pytest.mark.parametrize("trend", ["rising", "falling", "jumps"])
+def test_attention_stage_when_scores_run_away_from_the_first_maximum(shape, trend):
+    """The attention kernel keeps the running maximum where it is for as long as the probabilities stay
+    far from overflow and falls back to the full online-softmax step when a block's row sum explodes.
+    Scores that climb by hundreds of nats along the keys (rising), that start at their maximum (falling)
+    and that jump up in a few places force that fall-back again and again; the stage is compared with
+    the oracle's materialised softmax."""
+    wl = W.scaled(SHAPES[shape], batch=2, seqlen=1100, min_seqlen=None)
+    cfg = B.config_of(wl)
+    T, dh, dl, nq = wl.seqlen, wl.head_dim, wl.latent_dim, wl.n_qgroups
+    rng = np.random.default_rng(7)
+    lens = [T, 700]
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    total = int(cu[-1])
+    kw, cw = wl.kv_width
+    pos = np.concatenate([np.arange(n) for n in lens]).astype(np.float32)
+    u = rng.standard_normal(dh).astype(np.float32)
+    u /= np.linalg.norm(u)
+    if trend == "rising":
+        amp = pos * 0.9                       # raw score q.k grows by ~0.9 * sqrt(d_h) per key
+    elif trend == "falling":
+        amp = (1200.0 - pos) * 0.9
+    else:
+        amp = np.where((pos.astype(np.int64) % 257) == 200, 400.0 + pos * 0.5, 0.0).astype(np.float32)
+    q = np.tile(u * np.sqrt(dh), (total, nq)) + rng.standard_normal((total, nq * dh)).astype(np.float32) * 0.1
+    k = np.tile(u, (total, kw // dh)) * amp[:, None] + rng.standard_normal((total, kw)).astype(np.float32) * 0.1
+    c = rng.standard_normal((total, cw)).astype(np.float32)
+    q, k, c = (W.round_to_dtype(v.astype(np.float32), wl.dtype) for v in (q, k, c))
+    out = torch.full((total, nq * dl), float("nan"), dtype=torch.bfloat16, device="cuda")
+    B.gta_prefill_attention(cfg, B.to_device(q, wl.dtype), B.to_device(k, wl.dtype), B.to_device(c, wl.dtype),
+                            torch.from_numpy(cu).cuda(), len(lens), total, max(lens), out)
+    torch.cuda.synchronize()
+    ocfg = U.oracle_config(wl)
+    got = U.f64(out)
+    for b, n in enumerate(lens):
+        sl = slice(cu[b], cu[b + 1])
+        Q = q[sl].astype(np.float64).reshape(n, nq, dh); K = k[sl].astype(np.float64).reshape(n, -1, dh)
+        C = c[sl].astype(np.float64).reshape(n, -1, dl)
+        for g in range(nq):
+            A = orc.attention_map_rows(ocfg, Q[:, g], np.arange(n), K[:, ocfg.k_of_group(g)])
+            ref = A @ C[:, ocfg.c_of_group(g)]
+            U.assert_close(got[sl, g * dl:(g + 1) * dl], ref, wl.dtype, f"{shape} {trend} seq {b} group {g}", abs_scale=2.5)
