@@ -326,31 +326,24 @@ __device__ __forceinline__ bf16x4 pack4(float a, float b, float c, float d) {
   return v;
 }
 
-// Workgroup -> tile mapping.  Consecutive workgroup ids land on different XCDs (8 of them, each
-// with its own L2); the remap gives every XCD a contiguous range of whole row strips, and walks that
-// range in column panels of 4 tiles with the row strip as the fast index: the 32 workgroups that run
-// together on an XCD then share 8 X strips and 4 weight strips (instead of 2-3 and all of them), and
-// the weights are streamed from memory once per panel instead of once per round.
+// Workgroup -> tile mapping.  Consecutive workgroup ids land on different XCDs (8 of them, each with
+// its own L2), and an XCD works through its ids in order, about 32 workgroups at a time.  The tiles are
+// put in one global order -- blocks of 8 row strips x 4 column tiles, row strip fastest inside a block,
+// blocks column-panel by column-panel inside a band of 8 row strips, band after band -- and XCD x takes
+// the x-th eighth of that order: the 32 workgroups that run together on an XCD then form one block,
+// share 8 X strips and 4 weight strips (every operand slice fetched into the L2 is used 4 or 8 times),
+// whatever the numbers of row strips and column tiles are.  Edge blocks are simply smaller.
 __device__ __forceinline__ void tile_of_block(int ntn, int ntm, int &mt, int &nt) {
-  const int nblk = ntn * ntm;
-  int id = blockIdx.x;
-  const int per = nblk / 8;
-  if (id < per * 8) {
-    const int x = id % 8, j = id / 8;
-    constexpr int PW = 4;
-    if (per % ntn == 0 && per / ntn >= 2) {
-      const int ms = per / ntn;                       // row strips of this XCD
-      const int full = (ntn / PW) * (ms * PW);        // tiles in complete panels
-      const int p = j < full ? j / (ms * PW) : ntn / PW;
-      const int within = j < full ? j % (ms * PW) : j - full;
-      mt = x * ms + within % ms;
-      nt = p * PW + within / ms;
-      return;
-    }
-    id = x * per + j;
-  }
-  mt = id / ntn;
-  nt = id % ntn;
+  constexpr int RB = 8, PW = 4;
+  const int nblk = ntn * ntm, id = blockIdx.x, per = nblk / 8;
+  const int pos = id < per * 8 ? (id % 8) * per + id / 8 : id;   // the last nblk % 8 tiles keep their place
+  const int band = pos / (RB * ntn);
+  int rem = pos - band * RB * ntn;
+  const int h = min(RB, ntm - band * RB);      // row strips of this band
+  const int panel = rem / (h * PW);
+  rem -= panel * h * PW;
+  mt = band * RB + rem % h;
+  nt = panel * PW + rem / h;
 }
 
 // ---- epilogue of the 256 x 256 tile through LDS -------------------------------------------------

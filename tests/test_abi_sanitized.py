@@ -30,11 +30,11 @@ def test_validation_layer_is_clean_under_address_and_ub_sanitizers():
         out, _ = p.communicate()
         assert p.returncode == 0, out[-3000:]
     drv = os.path.join(OUT, "driver.o")
-    subprocess.run([HIPCC, "-x", "c", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined", "-g",
+    subprocess.run([HIPCC, "-x", "c", "-fno-gpu-sanitize", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined", "-g",
                     "-I", os.path.join(ROOT, "include"), "-c", os.path.join(ROOT, "tests", "abi_sanitize_driver.c"),
                     "-o", drv], check=True, capture_output=True, text=True)
     exe = os.path.join(OUT, "abi_sanitize_driver")
-    link = subprocess.run([HIPCC, "--offload-arch=gfx950", "-fsanitize=address,undefined", *objs, drv, "-o", exe],
+    link = subprocess.run([HIPCC, "--offload-arch=gfx950", "-fno-gpu-sanitize", "-fsanitize=address,undefined", *objs, drv, "-o", exe],
                           capture_output=True, text=True)
     assert link.returncode == 0, link.stderr[-3000:]
     env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0:abort_on_error=0", UBSAN_OPTIONS="print_stacktrace=1:halt_on_error=1")
