@@ -255,6 +255,12 @@ def bench_prefill(wl, steps, warmup, want_cpu_baseline):
                        "traffic": recorded_traffic(wl.name, "attn_prefill_kernel"),
                        "us_per_launch": ksec * 1e6, "us_per_launch_median": _event_median(attn_only, reps) * 1e6,
                        "algorithmic_flops_per_launch": fl["attn"]}
+    # the same launch on all-zero operands: identical instruction stream and addresses, no operand bits
+    # toggling -- how much of the kernel's time is the chip's power limit rather than its schedule
+    zq, zk, zc = torch.zeros_like(qd), torch.zeros_like(kd), torch.zeros_like(cd)
+    zsec = _event_time(lambda: B.gta_prefill_attention(cfg, zq, zk, zc, cud, wl.batch, total, max_seq, ld), reps)
+    res["roofline"]["us_per_launch_on_zero_operands"] = zsec * 1e6
+    del zq, zk, zc
     # the other kernels of the call, each alone through its stage entry point (same launch configuration
     # as inside gta_prefill): projection GEMM with RoPE, value-decoder GEMM with the gate, and the optional
     # output projection (not part of the timed gta_prefill call above, which runs without W_O)
@@ -496,16 +502,15 @@ def measured_ceilings():
     t_rd = _event_time(rd, 20)
     del bufs
     wgs, iters = 1024, 2000
-
-    def mm():
-        B.gta_calibration_mfma(wgs, iters, sink)
-
-    t_mm = _event_time(mm, 5)
     fl = wgs * 4 * iters * 16 * 32768.0
+    t_mm = _event_time(lambda: B.gta_calibration_mfma(wgs, iters, False, sink), 5)
+    t_mr = _event_time(lambda: B.gta_calibration_mfma(wgs, iters, True, sink), 5)
     return {"hbm_read_GBps": nbytes / t_rd / 1e9, "hbm_read_frac_of_peak": nbytes / t_rd / 1e9 / PEAK_HBM_GBPS,
-            "mfma_bf16_TFLOPs": fl / t_mm / 1e12, "mfma_bf16_frac_of_peak": fl / t_mm / 1e12 / PEAK_BF16_TFLOPS,
+            "mfma_bf16_TFLOPs": fl / t_mr / 1e12, "mfma_bf16_frac_of_peak": fl / t_mr / 1e12 / PEAK_BF16_TFLOPS,
+            "mfma_bf16_constant_operands_TFLOPs": fl / t_mm / 1e12,
             "what": "gta_calibration_read (512 MiB, 512 workgroups, non-temporal loads) and gta_calibration_mfma "
-                    "(1024 workgroups x 4 waves x 32000 v_mfma_f32_32x32x16_bf16, nothing else), timed here"}
+                    "(1024 workgroups x 4 waves x 32000 v_mfma_f32_32x32x16_bf16, nothing else; operands spread like "
+                    "activations and weights and rotating, which is what mfma_bf16_TFLOPs is, and one constant pair), timed here"}
 
 
 def main():

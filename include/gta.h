@@ -265,8 +265,12 @@ GTA_API int gta_calibration_read(const void *src, int64_t bytes, int32_t workgro
 /* Roofline calibration: `workgroups` workgroups of four waves, each wave issuing iters * 16
  * v_mfma_f32_32x32x16_bf16 (32768 flop each) on 16 independent accumulators and nothing else.  Timed
  * by the caller it gives the bf16 MFMA rate the chip sustains at the clock it holds under matrix load,
- * next to the published 2.5 PFLOP/s.  `sink`: device memory of at least 1 KiB. */
-GTA_API int gta_calibration_mfma(int32_t workgroups, int32_t iters, void *sink, void *hip_stream);
+ * next to the published 2.5 PFLOP/s.  random_operands 0: one pair of small constant operands;
+ * 1: eight operand pairs per lane with values spread like activations and weights, used in rotation
+ * (the rate is power-limited and depends on how many operand bits change between instructions).
+ * `sink`: device memory of at least 1 KiB. */
+GTA_API int gta_calibration_mfma(int32_t workgroups, int32_t iters, int32_t random_operands, void *sink,
+                                 void *hip_stream);
 
 /* Static string for a gta_status value. */
 GTA_API const char *gta_strerror(int code);

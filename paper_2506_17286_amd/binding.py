@@ -99,7 +99,7 @@ def load(path: Optional[str] = None) -> ctypes.CDLL:
     lib.gta_calibration_read.restype = ctypes.c_int
     lib.gta_calibration_read.argtypes = [vp, i64, ctypes.c_int32, vp, vp]
     lib.gta_calibration_mfma.restype = ctypes.c_int
-    lib.gta_calibration_mfma.argtypes = [ctypes.c_int32, ctypes.c_int32, vp, vp]
+    lib.gta_calibration_mfma.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, vp, vp]
     lib.gta_strerror.restype = ctypes.c_char_p
     lib.gta_strerror.argtypes = [ctypes.c_int]
     lib.gta_uses_tuned_kernels.restype = ctypes.c_int
@@ -299,8 +299,8 @@ def gta_calibration_read(src, nbytes: int, workgroups: int, sink, stream=None) -
     return rc
 
 
-def gta_calibration_mfma(workgroups: int, iters: int, sink, stream=None) -> int:
-    rc = load().gta_calibration_mfma(workgroups, iters, _ptr(sink), _stream(stream))
+def gta_calibration_mfma(workgroups: int, iters: int, random_operands: bool, sink, stream=None) -> int:
+    rc = load().gta_calibration_mfma(workgroups, iters, int(bool(random_operands)), _ptr(sink), _stream(stream))
     _check(rc, "gta_calibration_mfma")
     return rc
 

@@ -463,11 +463,12 @@ int gta_calibration_read(const void *src, int64_t bytes, int32_t workgroups, voi
   return launch_calibration_read(src, bytes, workgroups, sink, (hipStream_t)hip_stream);
 }
 
-int gta_calibration_mfma(int32_t workgroups, int32_t iters, void *sink, void *hip_stream) {
+int gta_calibration_mfma(int32_t workgroups, int32_t iters, int32_t random_operands, void *sink, void *hip_stream) {
   if (!sink) return GTA_ERR_NULL;
   if (workgroups <= 0 || workgroups > 65535 || iters <= 0) return GTA_ERR_SHAPE;
   if (misaligned(sink)) return GTA_ERR_ALIGN;
-  return launch_calibration_mfma(workgroups, iters, sink, (hipStream_t)hip_stream);
+  if (random_operands != 0 && random_operands != 1) return GTA_ERR_DTYPE;
+  return launch_calibration_mfma(workgroups, iters, random_operands == 1, sink, (hipStream_t)hip_stream);
 }
 
 int gta_cache_append(const gta_config *cfg, const gta_cache *cache, const int32_t *slots, const void *k_new,

@@ -604,13 +604,32 @@ __global__ __launch_bounds__(256) void calibration_read_kernel(const cal_u32x4 *
 // SIMD): the rate the matrix pipes sustain at the clock the chip holds under that load.
 typedef __attribute__((ext_vector_type(8))) __bf16 cal_bf16x8;
 typedef __attribute__((ext_vector_type(16))) float cal_f32x16;
+// RANDOM: eight operand pairs per lane with values spread like the workloads' activations (about
+// N(0,1)) and weights (about N(0,0.02)), used in rotation, so that the operand bits the matrix pipes
+// see change from one instruction to the next as they do inside a GEMM; otherwise one pair of small
+// constants.  What the chip sustains differs by a quarter between the two: it is power-limited.
+__device__ __forceinline__ unsigned cal_hash(unsigned x) {
+  x ^= x >> 16; x *= 0x7feb352du; x ^= x >> 15; x *= 0x846ca68bu; x ^= x >> 16;
+  return x;
+}
+template <bool RANDOM>
 __global__ __launch_bounds__(256) void calibration_mfma_kernel(int iters, float *sink) {
-  cal_bf16x8 x, y;
+  constexpr int NS = RANDOM ? 8 : 1;
+  cal_bf16x8 x[NS], y[NS];
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    x[i] = (__bf16)(0.001f * (float)((threadIdx.x * 7 + i) % 13) - 0.006f);
-    y[i] = (__bf16)(0.002f * (float)((threadIdx.x * 5 + i) % 11) - 0.01f);
-  }
+  for (int s = 0; s < NS; ++s)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      if (RANDOM) {
+        const unsigned h1 = cal_hash(threadIdx.x * 977u + s * 131u + i * 7u + blockIdx.x * 7919u), h2 = cal_hash(h1 + 12345u);
+        const float u = ((float)(h1 & 0xffff) + (float)(h1 >> 16) + (float)(h2 & 0xffff) + (float)(h2 >> 16)) / 65536.0f - 2.0f;
+        x[s][i] = (__bf16)(u * 1.7f);
+        y[s][i] = (__bf16)(-u * 0.034f + 0.001f * (float)i);
+      } else {
+        x[s][i] = (__bf16)(0.001f * (float)((threadIdx.x * 7 + i) % 13) - 0.006f);
+        y[s][i] = (__bf16)(0.002f * (float)((threadIdx.x * 5 + i) % 11) - 0.01f);
+      }
+    }
   cal_f32x16 acc[16];
 #pragma unroll
   for (int t = 0; t < 16; ++t)
@@ -618,7 +637,8 @@ __global__ __launch_bounds__(256) void calibration_mfma_kernel(int iters, float 
     for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
   for (int it = 0; it < iters; ++it)
 #pragma unroll
-    for (int t = 0; t < 16; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x, y, acc[t], 0, 0, 0);
+    for (int t = 0; t < 16; ++t)
+      acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x[t % NS], y[(t + t / NS) % NS], acc[t], 0, 0, 0);
   float v = 0.f;
 #pragma unroll
   for (int t = 0; t < 16; ++t) v += acc[t][0] + acc[t][15];
@@ -889,8 +909,9 @@ int launch_calibration_read(const void *src, int64_t bytes, int workgroups, void
   return check_launch();
 }
 
-int launch_calibration_mfma(int workgroups, int iters, void *sink, hipStream_t st) {
-  calibration_mfma_kernel<<<workgroups, 256, 0, st>>>(iters, (float *)sink);
+int launch_calibration_mfma(int workgroups, int iters, bool random_operands, void *sink, hipStream_t st) {
+  if (random_operands) calibration_mfma_kernel<true><<<workgroups, 256, 0, st>>>(iters, (float *)sink);
+  else calibration_mfma_kernel<false><<<workgroups, 256, 0, st>>>(iters, (float *)sink);
   return check_launch();
 }
 

@@ -158,7 +158,7 @@ void generic_decode_combine(const Dims &d, const float *part, const int32_t *old
                             hipStream_t st);
 int launch_calibration_copy(const void *src, void *dst, int64_t bytes, hipStream_t st);
 int launch_calibration_read(const void *src, int64_t bytes, int workgroups, void *sink, hipStream_t st);
-int launch_calibration_mfma(int workgroups, int iters, void *sink, hipStream_t st);
+int launch_calibration_mfma(int workgroups, int iters, bool random_operands, void *sink, hipStream_t st);
 void launch_rowmap(const int32_t *cu, int batch, int64_t total, int32_t *seq_id, int32_t *pos,
                    hipStream_t st);
 void launch_rope_table(float2 *tab, int max_pos, int dh, double base, hipStream_t st);

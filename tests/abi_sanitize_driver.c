@@ -115,7 +115,8 @@ int main(void) {
   EXPECT(gta_calibration_copy(fake, fake, 24, NULL), GTA_ERR_SHAPE);
   EXPECT(gta_calibration_copy(fake, fake, 0, NULL), GTA_OK);
   EXPECT(gta_calibration_read(fake, 1 << 20, 7, fake, NULL), GTA_ERR_SHAPE);
-  EXPECT(gta_calibration_mfma(0, 1, fake, NULL), GTA_ERR_SHAPE);
+  EXPECT(gta_calibration_mfma(0, 1, 0, fake, NULL), GTA_ERR_SHAPE);
+  EXPECT(gta_calibration_mfma(4, 1, 7, fake, NULL), GTA_ERR_DTYPE);
   EXPECT(strcmp(gta_strerror(GTA_ERR_WORKSPACE), "workspace missing or too small"), 0);
   EXPECT(strcmp(gta_strerror(-99), "unknown gta_status"), 0);
 
