@@ -84,6 +84,24 @@ PrefillWs carve_prefill(const Dims &d, bool tuned, bool with_wo, int batch, int6
   return w;
 }
 
+// Relative time of one split-K launch of `batch` sequences in `s` splits on kernels that keep one workgroup
+// per CU busy.  Measured at the 1B shape, 8K rows: one workgroup streams about 46 GB/s, so about 124 of them
+// saturate the memory system and anything from 124 to 256 workgroups takes the same time give or take 6 %
+// (the larger launches being the faster ones); past 256 the launch runs in rounds, and a last round of a few
+// workgroups costs a whole slice at one workgroup's rate (batch 96: 288 workgroups 360 us, 192 workgroups
+// 290 us; batch 72: 288 -> 280 us, 216 -> 227 us; batch 192: 384 -> 584 us, 192 -> 540 us).
+static double split_launch_cost(int batch, int s, int max_seq) {
+  const double kSaturating = 124.0;
+  const int64_t w = (int64_t)batch * s;
+  const int64_t full = w / 256, rem = w % 256;
+  double rounds = full * (256.0 / kSaturating);
+  if (rem) rounds += rem > kSaturating ? rem / kSaturating : 1.0;
+  const double rows = (double)((max_seq + s - 1) / s);
+  double cost = rows * rounds;
+  if (w <= 256) cost *= 1.0 - 0.15 * (double)w / 256.0;
+  return cost + 0.5 * s;   // partials to write and merge
+}
+
 int choose_splits(const Dims &d, int batch, int max_seq, int requested) {
   if (requested > 0) return requested > 1024 ? 1024 : requested;
   // enough (sequence, split) blocks to put one or two on every one of the 256 CUs (the kernel's choice), but
@@ -92,10 +110,21 @@ int choose_splits(const Dims &d, int batch, int max_seq, int requested) {
   int want = (target + batch - 1) / batch;
   int cap = max_seq / 256;
   if (cap < 1) cap = 1;
-  if (tuned_decode_supported(d)) cap = std::min(cap, tuned_decode_max_splits(d, batch));
+  const bool tuned = tuned_decode_supported(d);
+  if (tuned) cap = std::min(cap, tuned_decode_max_splits(d, batch));
+  cap = std::min(cap, 256);
+  if (tuned && target == 256) {
+    // one workgroup per CU: the split count whose launch fills whole rounds of 256
+    int best = 1;
+    double best_cost = split_launch_cost(batch, 1, max_seq);
+    for (int s = 2; s <= cap && (int64_t)batch * s <= 1024; ++s) {
+      const double c = split_launch_cost(batch, s, max_seq);
+      if (c < best_cost) { best_cost = c; best = s; }
+    }
+    return best;
+  }
   int s = want < cap ? want : cap;
   if (s < 1) s = 1;
-  if (s > 256) s = 256;
   return s;
 }
 

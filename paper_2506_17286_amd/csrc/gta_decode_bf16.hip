@@ -1324,7 +1324,8 @@ void launch_tail_any(const Dims &d, const float *pacc, const float *pml, const D
                      const bf16 *wp, TO *out, const gta_cache &cache, const int32_t *slots, hipStream_t st) {
   // about 512 workgroups (two per CU): one sequence per workgroup up to batch * n_h = 512, then 2, 4, 8.
   // Measured at the 1B shape, 8K context: batch 16 one-sequence kernel 9 us against 16 us with two rows;
-  // batch 64 two rows 18 us against 31 us with eight; batch 128 four rows 24 us against 30 us with two.
+  // batch 64 two rows 18 us against 31 us with eight (and a whole step of 205 us against 214 us with the
+  // one-sequence kernel); batch 128 four rows 24 us against 30 us with two.
   const int rows = batch * d.nh / 512;
   if (rows < 2 && d.dl == 512 && d.dh == 128 && ws.splits <= 64) {
     decode_tail1_kernel<TO><<<dim3(d.nh, batch), 512, 0, st>>>(d, pacc, pml, ws.oldlen, ws.splits, gs.g, gs.nsum,
