@@ -411,6 +411,16 @@ __global__ __launch_bounds__(T::NT) void proj_gemm_kernel(ProjArgs a) {
   const int m0 = mt * T::BM;
   f32x16 acc[T::TN][T::TM];
   zero_acc<T>(acc);
+  // positions of this lane's rows: asked for before the main loop (a tile of Q or K rotates by them right
+  // after it: 0.8 us of load latency per tile otherwise), not at all by the big tiles that do not rotate
+  const bool rotate = a.rope != nullptr && seg < 2;
+  constexpr bool kBig = T::TM == 4 && T::TN == 4;
+  int pos_of[T::TM];
+  if (rotate || !kBig) {
+#pragma unroll
+    for (int tm = 0; tm < T::TM; ++tm)
+      pos_of[tm] = a.pos[min(m0 + (int)(threadIdx.x >> 6) / T::WGN * T::WM + tm * 32 + (int)(threadIdx.x & 31), a.M - 1)];
+  }
   if constexpr (T::TM == 4 && T::TN == 4) {
     const int ldb = a.width[seg];
     const unsigned boff = (unsigned)((threadIdx.x / (T::BN / 8)) * ldb + (threadIdx.x % (T::BN / 8)) * 8) * 2u;
@@ -425,14 +435,14 @@ __global__ __launch_bounds__(T::NT) void proj_gemm_kernel(ProjArgs a) {
   const int wn = wave % T::WGN, wm = wave / T::WGN;
   const int nw = n_glob + wn * T::WN;            // first column of this wave inside its segment
   const int half = a.dh / 2;
-  const bool rotate = a.rope != nullptr && seg < 2;
   bf16 *cache = seg == 1 ? a.kcache : (seg == 2 ? a.ccache : nullptr);
   const int width = a.width[seg];
+  if (rotate || !kBig)
 #pragma unroll
   for (int tm = 0; tm < T::TM; ++tm) {
     const int m = m0 + wm * T::WM + tm * 32 + (lane & 31);
     if (m >= a.M) continue;
-    const int p = a.pos[m];
+    const int p = pos_of[tm];
     const int rrow = a.rope_by_token ? m : p;   // RoPE table row
     if (rotate && (a.rope_by_token || p < a.max_len)) {
       // wave tile spans whole heads (WN % d_h == 0); pair column j with j + d_h/2 of the same head
