@@ -437,7 +437,47 @@ __global__ __launch_bounds__(T::NT) void proj_gemm_kernel(ProjArgs a) {
   const int half = a.dh / 2;
   bf16 *cache = seg == 1 ? a.kcache : (seg == 2 ? a.ccache : nullptr);
   const int width = a.width[seg];
-  if (rotate || !kBig)
+  if constexpr (kBig) {
+    if (rotate) {
+      // wave tile = one head: column j pairs with j + d_h/2.  32 groups of 4 pairs per lane (4 row blocks x
+      // 2 column blocks x 4 register quads); the table values of a group are asked for two groups ahead of
+      // their use (one after the other, every group would wait out a whole memory round trip: 9 us per tile)
+      constexpr int tiles_half = kHeadDim / 64;
+      static_assert(T::TN == 2 * tiles_half, "a wave tile of the rotating segments is one head wide");
+      constexpr int G = T::TM * tiles_half * 4, AHEAD = 2;
+      bool rot[T::TM];
+      const float2 *trow[T::TM];
+#pragma unroll
+      for (int tm = 0; tm < T::TM; ++tm) {
+        const int m = m0 + wm * T::WM + tm * 32 + (lane & 31), p = pos_of[tm];
+        rot[tm] = m < a.M && (a.rope_by_token || p < a.max_len);
+        // rows that do not rotate read row 0 of the table and keep their values
+        trow[tm] = a.rope + (int64_t)(rot[tm] ? (a.rope_by_token ? m : p) : 0) * half + (lane >> 5) * 4;
+      }
+      float4 tv[AHEAD + 1][2];
+      auto ask = [&](int g) {
+        const int tm = g / (tiles_half * 4), tn = (g / 4) % tiles_half, rq = g % 4;
+        const float4 *tp = reinterpret_cast<const float4 *>(trow[tm] + tn * 32 + rq * 8);
+        tv[g % (AHEAD + 1)][0] = tp[0]; tv[g % (AHEAD + 1)][1] = tp[1];
+      };
+#pragma unroll
+      for (int g = 0; g < AHEAD; ++g) ask(g);
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        if (g + AHEAD < G) ask(g + AHEAD);
+        const int tm = g / (tiles_half * 4), tn = (g / 4) % tiles_half, rq = g % 4, tn_hi = tn + tiles_half;
+        const float4 t0 = tv[g % (AHEAD + 1)][0], t1 = tv[g % (AHEAD + 1)][1];
+        const float cs[4] = {t0.x, t0.z, t1.x, t1.z}, sn[4] = {t0.y, t0.w, t1.y, t1.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const float lo = acc[tn][tm][rq * 4 + i], hi = acc[tn_hi][tm][rq * 4 + i];
+          acc[tn][tm][rq * 4 + i] = rot[tm] ? lo * cs[i] - hi * sn[i] : lo;
+          acc[tn_hi][tm][rq * 4 + i] = rot[tm] ? hi * cs[i] + lo * sn[i] : hi;
+        }
+      }
+    }
+  }
+  if constexpr (!kBig)
 #pragma unroll
   for (int tm = 0; tm < T::TM; ++tm) {
     const int m = m0 + wm * T::WM + tm * 32 + (lane & 31);
@@ -467,7 +507,6 @@ __global__ __launch_bounds__(T::NT) void proj_gemm_kernel(ProjArgs a) {
         }
       }
     }
-    if constexpr (T::TM == 4 && T::TN == 4) continue;   // stored below through LDS
     bf16 *drow = a.dst[seg] + (int64_t)m * width + nw;
     bf16 *crow = nullptr;
     if (cache) {
