@@ -123,6 +123,10 @@ int choose_splits(const Dims &d, int batch, int max_seq, int requested) {
     }
     return best;
   }
+  // two workgroups per CU: a launch of just over 512 workgroups runs a second round for the few left over
+  // (paper layer, 2K rows, whole step: batch 72 54 us with 8 splits, 42.5 us with 7; batch 96 57 -> 47;
+  // batch 160 73 -> 60), so the count is rounded down to what fits
+  if (tuned && batch <= target && (int64_t)batch * want > target) want = target / batch;
   int s = want < cap ? want : cap;
   if (s < 1) s = 1;
   return s;
